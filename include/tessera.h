@@ -1,0 +1,280 @@
+/*
+ * tessera.h - C ABI of the MI355X (gfx950) decoder-layer kernel library.
+ *
+ * The paper schedules the kernels of one LLM forward iteration, one by one,
+ * across GPUs (kernel-granularity disaggregation, Sec. 3).  It treats those
+ * kernels as opaque framework kernels with declared read and write buffers
+ * (Sec. 3.1) and characterises them only by regime: skinny matrix products are
+ * HBM-bandwidth-bound, tiled prefill attention is compute-bound (Sec. 2.3).
+ * This library IS that kernel set for one decoder layer, one entry point per
+ * kernel, plus the whole-layer call and the pipelined micro-batch step with
+ * boundary-activation copies on a side stream (Sec. 3.3, "Disaggregated kernel
+ * execution" and "Pipelined request processing").
+ *
+ * Conventions that hold for every entry point unless stated otherwise:
+ *   - All tensor pointers are DEVICE pointers (HIP global memory) unless the
+ *     parameter comment says "host".  Integer index arrays are device int32.
+ *   - ts_bf16 is the raw 16-bit pattern of a bfloat16.  Tensors are row-major,
+ *     innermost dimension contiguous, no padding.
+ *   - Every device pointer must be 16-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work; they never synchronise, allocate or free device
+ *     memory.  The caller owns every buffer and keeps it alive (and does not
+ *     overwrite inputs) until the enqueued work has finished.
+ *   - Accumulation is fp32; results are rounded once (nearest-even) to bf16.
+ *   - Return value: TS_OK or a negative TS_ERR_* code.  On error nothing has
+ *     been enqueued.  Argument checks run before the first HIP call, so they
+ *     work on a host without a GPU.  ts_last_error() gives a thread-local
+ *     detail string for the last failing call on this thread.
+ *   - Output buffers must not alias inputs except where a parameter is
+ *     documented as in/out.
+ */
+#ifndef TESSERA_H_
+#define TESSERA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+#if defined(__GNUC__)
+#pragma GCC visibility push(default) /* the library is built with hidden visibility */
+#endif
+
+typedef uint16_t ts_bf16;
+
+#define TS_OK 0
+#define TS_ERR_INVALID_ARG (-1)       /* null pointer, non-positive size, nq % nkv != 0, misaligned pointer */
+#define TS_ERR_UNSUPPORTED_SHAPE (-2) /* valid but outside what the kernels cover (see each call) */
+#define TS_ERR_WORKSPACE (-3)         /* workspace / staging buffer too small or missing */
+#define TS_ERR_HIP (-4)               /* a HIP runtime call failed; see ts_last_error() */
+
+#define TS_MODE_DECODE 0
+#define TS_MODE_PREFILL 1
+
+/* Text for a status code (static storage). */
+const char* ts_strerror(int code);
+/* Detail of the last error raised on the calling thread (thread-local storage, never NULL). */
+const char* ts_last_error(void);
+/* Library version string (static storage). */
+const char* ts_version(void);
+
+/* ---------------------------------------------------------------------------
+ * RMSNorm: y[t,i] = x[t,i] * rsqrt(mean_j x[t,j]^2 + eps) * gamma[i].
+ * One of the small memory-bound kernels of the layer (Sec. 2.3 regime split).
+ * x, y: [T,H]; gamma: [H].  y may alias x.  Requires H % 8 == 0, H <= 32768.
+ * T == 0 is a no-op.
+ */
+int ts_rmsnorm(const ts_bf16* x, const ts_bf16* gamma, ts_bf16* y, int T, int H, float eps, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Dense projection C = A * W^T (+ residual): the layer's QKV, O, gate|up and
+ * down products.  With few rows this is the paper's bandwidth-bound
+ * matrix-vector regime (weights streamed once from HBM); with thousands of
+ * rows it is the compute-bound regime (Sec. 2.3).
+ * A: [M,K]; W: [N,K]; residual: [M,N] or NULL; C: [M,N].  C may alias residual.
+ * Requires K % 8 == 0 and N % 2 == 0.  M == 0 is a no-op.
+ * ws: scratch of at least ts_gemm_workspace_bytes(M,N,K) bytes (may be NULL
+ * when that is 0).  Contents of ws are undefined afterwards.
+ */
+size_t ts_gemm_workspace_bytes(int M, int N, int K);
+int ts_gemm_bf16(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, ts_bf16* C,
+                 int M, int N, int K, void* ws, size_t ws_bytes, void* stream);
+/* Same product with an fp32 result (router logits of the MoE layer). No residual. */
+int ts_gemm_bf16_f32out(const ts_bf16* A, const ts_bf16* W, float* C,
+                        int M, int N, int K, void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Rotary embedding (rotate-half pairing (i, i + d/2), theta_i = base^(-2i/d),
+ * angle = pos * theta_i) applied in place to q and k, followed by the KV-cache
+ * append: the cache is the buffer written in one iteration and read by later
+ * ones (cross-iteration dependency, Sec. 3.1), and the appended rows are the
+ * "delta" that would be replicated between GPUs (Sec. 4, memory management).
+ * q: [T,nq,d] in/out with row stride `q_stride` elements between tokens;
+ * k: [T,nkv,d] in/out, v: [T,nkv,d] in, both with row stride `kv_stride`.
+ *   (strides let q,k,v live inside one [T,(nq+2nkv)d] projection output.)
+ * pos: [T] position of each token; seq_id: [T] cache row of each token (may be
+ * NULL when kcache is NULL).  cos_sin: optional fp32 table [table_len, d]
+ * (row p = cos(p*theta_0..d/2-1) then sin(...)), built by ts_rope_table; when
+ * NULL the angles are evaluated in fp64 inside the kernel.
+ * kcache, vcache: [B,nkv,Lcap,d] or both NULL to skip the append.  Rotated k and
+ * v of token t go to cache[seq_id[t], :, pos[t], :].
+ * Requires d % 16 == 0, d <= 256, strides % 8 == 0.  Positions outside
+ * [0,Lcap) (or [0,table_len) with a table) are the caller's error; tokens with
+ * such positions are skipped for the append and rotated with the fp64 path.
+ */
+int ts_rope(ts_bf16* q, ts_bf16* k, const ts_bf16* v, int q_stride, int kv_stride,
+            const int32_t* pos, const int32_t* seq_id, const float* cos_sin, int table_len,
+            ts_bf16* kcache, ts_bf16* vcache, int T, int nq, int nkv, int d, int Lcap,
+            float base, void* stream);
+/* Host helper: fill a HOST buffer table[table_len*d] with the fp32 cos|sin table (fp64 evaluation). */
+int ts_rope_table(float* table_host, int table_len, int d, float base);
+
+/* ---------------------------------------------------------------------------
+ * Decode attention over the contiguous KV cache: the large bandwidth-bound
+ * kernel of a decode iteration (K and V are each read once).
+ * For sequence b and query head h (kv head h / (nq/nkv)), over keys
+ * j in [0, seq_lens[b]):  out = softmax_j(scale * <q, K_j>) . V
+ * q, out: [B,nq,d]; kcache, vcache: [B,nkv,Lcap,d]; seq_lens: [B] (number of
+ * keys attended, the just-appended token included; 0 gives a zero row).
+ * Requires d == 64 or d == 128, nq/nkv <= 16, seq_lens[b] <= Lcap.
+ * ws: at least ts_attention_decode_workspace_bytes(B,nq,d,Lcap) bytes.
+ */
+size_t ts_attention_decode_workspace_bytes(int B, int nq, int nkv, int d, int Lcap);
+int ts_attention_decode(const ts_bf16* q, const ts_bf16* kcache, const ts_bf16* vcache,
+                        const int32_t* seq_lens, ts_bf16* out, int B, int nq, int nkv, int d,
+                        int Lcap, float scale, void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Prefill attention over packed fresh sequences: the compute-bound tiled
+ * kernel (Sec. 2.3).  Token at in-sequence index i attends keys j <= i of its
+ * own sequence when `causal` != 0, all keys of its sequence otherwise.
+ * q: [T,nq,d] row stride q_stride; k, v: [T,nkv,d] row stride kv_stride;
+ * cu_seqlens: [S+1] device int32, sequence s owns rows cu[s]..cu[s+1]-1, cu[S] <= T;
+ * out: [T,nq,d] dense.  max_seqlen: host-known upper bound on any sequence
+ * length (sizes the grid).  Requires d == 64 or d == 128.
+ */
+int ts_attention_prefill(const ts_bf16* q, const ts_bf16* k, const ts_bf16* v, int q_stride,
+                         int kv_stride, const int32_t* cu_seqlens, ts_bf16* out, int S, int T,
+                         int max_seqlen, int nq, int nkv, int d, float scale, int causal,
+                         void* stream);
+
+/* ---------------------------------------------------------------------------
+ * SwiGLU: out[t,f] = silu(gate_up[t,f]) * gate_up[t,F+f], silu(z) = z/(1+exp(-z)).
+ * gate_up: [T,2F] = [gate | up]; out: [T,F].  Requires F % 8 == 0.
+ */
+int ts_swiglu(const ts_bf16* gate_up, ts_bf16* out, int T, int F, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * MoE routing from fp32 logits[T,E]: per token the k largest logits (ties to
+ * the lower expert index, slots in descending-logit order), weights = softmax
+ * over the k selected logits, per-expert counts, exclusive offsets[E+1], and
+ * perm[T*k]: flat assignment ids a = t*k+s grouped by expert, ascending inside
+ * each expert (deterministic).  Integer outputs are exact.
+ * Requires 1 <= k <= E <= 64, T*k <= 2^20.
+ */
+int ts_moe_route(const float* logits, int T, int E, int k, int32_t* topk_idx, float* topk_w,
+                 int32_t* counts, int32_t* offsets, int32_t* perm, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Grouped expert projection: for expert e and grouped row r in
+ * [offsets[e], offsets[e+1]):  C[r,:] = A[src(r),:] * W[e]^T, with
+ * src(r) = row_map[r] / row_div when row_map != NULL (gather; pass perm and
+ * row_div = k to read token rows), else src(r) = r.
+ * A: [*,K]; W: [E,N,K]; offsets: [E+1] device; C: [rows,N] where rows is the
+ * host-known total offsets[E].  All E weight matrices are streamed from HBM
+ * once per call when every expert has at most 128 rows (bandwidth-bound).
+ * Requires K % 8 == 0, N % 2 == 0.  No workspace.
+ */
+int ts_moe_gemm(const ts_bf16* A, const int32_t* row_map, int row_div, const ts_bf16* W,
+                const int32_t* offsets, ts_bf16* C, int rows, int E, int N, int K, void* stream);
+
+/* out[t,:] = residual[t,:] + sum_s topk_w[t,s] * y[r(t,s),:], perm[r(t,s)] = t*k+s.
+ * y: [T*k,H] grouped order; perm: [T*k]; topk_w: [T,k] fp32; residual: [T,H] or NULL; out: [T,H].
+ * scratch_inv: device int32[T*k] scratch (inverse permutation), contents undefined afterwards.
+ * Requires H % 8 == 0.
+ */
+int ts_moe_combine(const ts_bf16* y, const int32_t* perm, const float* topk_w,
+                   const ts_bf16* residual, ts_bf16* out, int32_t* scratch_inv, int T, int k, int H,
+                   void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Whole decoder layer on one stream, no host synchronisation inside:
+ *   rmsnorm -> QKV -> rope + KV append -> attention -> O (+x) -> rmsnorm ->
+ *   dense:  gate|up -> swiglu -> down (+x2)
+ *   MoE:    router logits -> route -> grouped gate|up -> swiglu -> grouped down -> combine (+x2)
+ * Every arrow is a separate kernel with a materialised buffer between, because
+ * those buffers are the edges the method may cut between GPUs (Sec. 3.1, 3.3).
+ */
+typedef struct ts_layer_desc {
+  int32_t H, nq, nkv, d, F;
+  int32_t E, k;          /* E == 0: dense MLP */
+  int32_t Lcap;          /* positions per cache row */
+  int32_t mode;          /* TS_MODE_DECODE | TS_MODE_PREFILL */
+  float eps, rope_base;
+} ts_layer_desc;
+
+typedef struct ts_layer_weights {
+  const ts_bf16* gamma1;    /* [H] */
+  const ts_bf16* w_qkv;     /* [(nq+2nkv)d, H], rows = q heads, then k heads, then v heads */
+  const ts_bf16* w_o;       /* [H, nq*d] */
+  const ts_bf16* gamma2;    /* [H] */
+  const ts_bf16* w_router;  /* [E,H] (MoE) or NULL */
+  const ts_bf16* w_gate_up; /* [2F,H] = [gate rows | up rows]; MoE: [E,2F,H] */
+  const ts_bf16* w_down;    /* [H,F]; MoE: [E,H,F] */
+  const float* rope_cos_sin;/* optional device table [rope_table_len, d] or NULL */
+  int32_t rope_table_len;
+} ts_layer_weights;
+
+typedef struct ts_layer_io {
+  const ts_bf16* x;          /* [T,H] */
+  ts_bf16* out;              /* [T,H] */
+  const int32_t* pos;        /* [T] */
+  const int32_t* seq_id;     /* [T] */
+  const int32_t* seq_lens;   /* decode: [B] keys attended after the append */
+  const int32_t* cu_seqlens; /* prefill: [B+1] */
+  ts_bf16* kcache;           /* [Bcache,nkv,Lcap,d], in/out */
+  ts_bf16* vcache;
+  int32_t T, B;
+  int32_t max_seqlen;        /* prefill: host-known bound on a sequence's token count */
+} ts_layer_io;
+
+/* Kernel-boundary buffers of the layer, in kernel order.  Dense layers have
+ * TS_NB_DENSE of them, MoE layers TS_NB_MOE. */
+enum {
+  TS_B_H1 = 0, TS_B_QKV = 1, TS_B_ATTN = 2, TS_B_X2 = 3, TS_B_H2 = 4,
+  TS_B_GATE_UP = 5, TS_B_ACT = 6,
+  TS_B_OUT_DENSE = 7, TS_NB_DENSE = 8,
+  TS_B_Y_MOE = 7, TS_B_OUT_MOE = 8, TS_NB_MOE = 9
+};
+
+/* Bytes of workspace ts_layer_forward needs for T tokens / B sequences (0 on invalid desc). */
+size_t ts_layer_workspace_bytes(const ts_layer_desc* desc, int T, int B);
+/* Where boundary `index` lives: byte offset inside the workspace (or (size_t)-1 for the last
+ * boundary, which is io->out) and its size in bytes.  Host-only arithmetic. */
+int ts_layer_boundary(const ts_layer_desc* desc, int T, int B, int index, size_t* ws_offset,
+                      size_t* bytes);
+/* Where the MoE routing outputs live inside the workspace (host-only arithmetic):
+ * offsets of logits f32[T,E], topk_idx i32[T,k], topk_w f32[T,k], counts i32[E], offsets i32[E+1], perm i32[T*k]. */
+int ts_layer_moe_buffers(const ts_layer_desc* desc, int T, int B, size_t ws_offsets[6]);
+int ts_layer_forward(const ts_layer_desc* desc, const ts_layer_weights* w, const ts_layer_io* io,
+                     void* ws, size_t ws_bytes, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Pipelined micro-batch step (Sec. 3.3): micro-batch i runs the layer on
+ * compute stream i % 2; after every flagged kernel boundary an event is
+ * recorded and, on the copy stream, the boundary tensor is packed into the
+ * micro-batch's contiguous staging slot and copied to pinned host memory (the
+ * stand-in for the `send` on a cut edge).  Compute streams never wait for the
+ * copy stream except before a workspace half is reused by a later micro-batch.
+ *
+ * ts_pipeline owns only HIP events.  boundary_mask bit i selects boundary i.
+ * Layout: ts_pipeline_boundary_layout gives, for the flagged boundaries in
+ * kernel order, byte offsets inside one micro-batch slot (offsets[n] = slot
+ * bytes).  Slot i of dev_staging / pinned_host starts at i * slot_stride where
+ * slot_stride = offsets[n] rounded up to 256.
+ * dev_staging: device, >= n_mb*slot_stride bytes.  pinned_host: HOST pinned
+ * memory of the same size.  ws: device, >= 2 * ts_layer_workspace_bytes(Tmax,Bmax)
+ * rounded up to 256 each, where Tmax/Bmax are the largest over micro-batches.
+ * All micro-batches must flag the same boundaries; their T may differ (the
+ * layout is computed for each T; slot_stride uses the largest).
+ * The call returns after enqueueing; the caller synchronises the three streams.
+ */
+typedef struct ts_pipeline ts_pipeline;
+int ts_pipeline_create(const ts_layer_desc* desc, int max_micro_batches, ts_pipeline** out);
+void ts_pipeline_destroy(ts_pipeline* p);
+int ts_pipeline_boundary_layout(const ts_layer_desc* desc, int T, int B, uint64_t boundary_mask,
+                                size_t* offsets /* host, [n+1] */, int* n_boundaries);
+size_t ts_pipeline_slot_stride(const ts_layer_desc* desc, int T, int B, uint64_t boundary_mask);
+int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_io* mb, int n_mb,
+                     void* compute_streams[2], void* copy_stream, uint64_t boundary_mask,
+                     int copy_on_compute_stream, void* dev_staging, void* pinned_host,
+                     size_t staging_bytes, void* ws, size_t ws_bytes);
+#if defined(__GNUC__)
+#pragma GCC visibility pop
+#endif
+#ifdef __cplusplus
+}
+#endif
+#endif /* TESSERA_H_ */

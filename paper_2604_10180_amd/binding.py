@@ -1,0 +1,266 @@
+"""ctypes binding of libtessera.so: same names as the C ABI, torch tensors in, status checked.
+
+PyTorch is used for device memory and streams only.  Pointers are taken with
+`data_ptr()`; no tensor is copied, converted or computed on here.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libtessera.so")
+
+TS_OK, TS_ERR_INVALID_ARG, TS_ERR_UNSUPPORTED_SHAPE, TS_ERR_WORKSPACE, TS_ERR_HIP = 0, -1, -2, -3, -4
+TS_MODE_DECODE, TS_MODE_PREFILL = 0, 1
+(TS_B_H1, TS_B_QKV, TS_B_ATTN, TS_B_X2, TS_B_H2, TS_B_GATE_UP, TS_B_ACT) = range(7)
+TS_B_OUT_DENSE, TS_NB_DENSE = 7, 8
+TS_B_Y_MOE, TS_B_OUT_MOE, TS_NB_MOE = 7, 8, 9
+
+EXPORTS = [
+    "ts_strerror", "ts_last_error", "ts_version", "ts_rmsnorm", "ts_gemm_workspace_bytes", "ts_gemm_bf16",
+    "ts_gemm_bf16_f32out", "ts_rope", "ts_rope_table", "ts_attention_decode_workspace_bytes",
+    "ts_attention_decode", "ts_attention_prefill", "ts_swiglu", "ts_moe_route", "ts_moe_gemm", "ts_moe_combine",
+    "ts_layer_workspace_bytes", "ts_layer_boundary", "ts_layer_moe_buffers", "ts_layer_forward",
+    "ts_pipeline_create", "ts_pipeline_destroy", "ts_pipeline_boundary_layout", "ts_pipeline_slot_stride",
+    "ts_pipeline_step",
+]
+
+
+class TesseraError(RuntimeError):
+    def __init__(self, code: int, detail: str):
+        super().__init__(f"tessera error {code}: {detail}")
+        self.code = code
+        self.detail = detail
+
+
+class LayerDesc(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("H", "nq", "nkv", "d", "F", "E", "k", "Lcap", "mode")] + \
+               [("eps", C.c_float), ("rope_base", C.c_float)]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("gamma1", "w_qkv", "w_o", "gamma2", "w_router", "w_gate_up", "w_down",
+                                          "rope_cos_sin")] + [("rope_table_len", C.c_int32)]
+
+
+class LayerIO(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("x", "out", "pos", "seq_id", "seq_lens", "cu_seqlens", "kcache", "vcache")] + \
+               [("T", C.c_int32), ("B", C.c_int32), ("max_seqlen", C.c_int32)]
+
+
+def _load() -> C.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2604_10180_amd.build` "
+                          "(there is no fallback path)")
+    lib = C.CDLL(LIB_PATH)
+    for n in ("ts_strerror", "ts_last_error", "ts_version"):
+        getattr(lib, n).restype = C.c_char_p
+    for n in ("ts_gemm_workspace_bytes", "ts_attention_decode_workspace_bytes", "ts_layer_workspace_bytes",
+              "ts_pipeline_slot_stride"):
+        getattr(lib, n).restype = C.c_size_t
+    lib.ts_pipeline_destroy.restype = None
+    return lib
+
+
+lib = _load()
+
+_i, _f, _p, _z, _u64 = C.c_int, C.c_float, C.c_void_p, C.c_size_t, C.c_uint64
+lib.ts_strerror.argtypes = [_i]
+lib.ts_rmsnorm.argtypes = [_p, _p, _p, _i, _i, _f, _p]
+lib.ts_gemm_workspace_bytes.argtypes = [_i, _i, _i]
+lib.ts_gemm_bf16.argtypes = [_p, _p, _p, _p, _i, _i, _i, _p, _z, _p]
+lib.ts_gemm_bf16_f32out.argtypes = [_p, _p, _p, _i, _i, _i, _p, _z, _p]
+lib.ts_rope.argtypes = [_p, _p, _p, _i, _i, _p, _p, _p, _i, _p, _p, _i, _i, _i, _i, _i, _f, _p]
+lib.ts_rope_table.argtypes = [_p, _i, _i, _f]
+lib.ts_attention_decode_workspace_bytes.argtypes = [_i, _i, _i, _i, _i]
+lib.ts_attention_decode.argtypes = [_p, _p, _p, _p, _p, _i, _i, _i, _i, _i, _f, _p, _z, _p]
+lib.ts_attention_prefill.argtypes = [_p, _p, _p, _i, _i, _p, _p, _i, _i, _i, _i, _i, _i, _f, _i, _p]
+lib.ts_swiglu.argtypes = [_p, _p, _i, _i, _p]
+lib.ts_moe_route.argtypes = [_p, _i, _i, _i, _p, _p, _p, _p, _p, _p]
+lib.ts_moe_gemm.argtypes = [_p, _p, _i, _p, _p, _p, _i, _i, _i, _i, _p]
+lib.ts_moe_combine.argtypes = [_p, _p, _p, _p, _p, _p, _i, _i, _i, _p]
+lib.ts_layer_workspace_bytes.argtypes = [C.POINTER(LayerDesc), _i, _i]
+lib.ts_layer_boundary.argtypes = [C.POINTER(LayerDesc), _i, _i, _i, C.POINTER(_z), C.POINTER(_z)]
+lib.ts_layer_moe_buffers.argtypes = [C.POINTER(LayerDesc), _i, _i, C.POINTER(_z)]
+lib.ts_layer_forward.argtypes = [C.POINTER(LayerDesc), C.POINTER(LayerWeights), C.POINTER(LayerIO), _p, _z, _p]
+lib.ts_pipeline_create.argtypes = [C.POINTER(LayerDesc), _i, C.POINTER(_p)]
+lib.ts_pipeline_destroy.argtypes = [_p]
+lib.ts_pipeline_boundary_layout.argtypes = [C.POINTER(LayerDesc), _i, _i, _u64, C.POINTER(_z), C.POINTER(_i)]
+lib.ts_pipeline_slot_stride.argtypes = [C.POINTER(LayerDesc), _i, _i, _u64]
+lib.ts_pipeline_step.argtypes = [_p, C.POINTER(LayerWeights), C.POINTER(LayerIO), _i, C.POINTER(_p), _p, _u64, _i,
+                                 _p, _p, _z, _p, _z]
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(s) -> Optional[int]:
+    if s is None:
+        return torch.cuda.current_stream().cuda_stream if torch.cuda.is_available() else None
+    if isinstance(s, int):
+        return s
+    return s.cuda_stream
+
+
+def _check(rc: int) -> None:
+    if rc != TS_OK:
+        raise TesseraError(rc, lib.ts_last_error().decode())
+
+
+def _nbytes(t) -> int:
+    return 0 if t is None else t.numel() * t.element_size()
+
+
+def ts_version() -> str:
+    return lib.ts_version().decode()
+
+
+def ts_strerror(code: int) -> str:
+    return lib.ts_strerror(code).decode()
+
+
+def ts_last_error() -> str:
+    return lib.ts_last_error().decode()
+
+
+def ts_rmsnorm(x, gamma, y, T: int, H: int, eps: float, stream=None) -> None:
+    _check(lib.ts_rmsnorm(_ptr(x), _ptr(gamma), _ptr(y), T, H, eps, _stream(stream)))
+
+
+def ts_gemm_workspace_bytes(M: int, N: int, K: int) -> int:
+    return lib.ts_gemm_workspace_bytes(M, N, K)
+
+
+def ts_gemm_bf16(A, W, residual, Cout, M: int, N: int, K: int, ws=None, stream=None) -> None:
+    _check(lib.ts_gemm_bf16(_ptr(A), _ptr(W), _ptr(residual), _ptr(Cout), M, N, K, _ptr(ws), _nbytes(ws),
+                            _stream(stream)))
+
+
+def ts_gemm_bf16_f32out(A, W, Cout, M: int, N: int, K: int, ws=None, stream=None) -> None:
+    _check(lib.ts_gemm_bf16_f32out(_ptr(A), _ptr(W), _ptr(Cout), M, N, K, _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def ts_rope(q, k, v, q_stride: int, kv_stride: int, pos, seq_id, cos_sin, table_len: int, kcache, vcache, T: int,
+            nq: int, nkv: int, d: int, Lcap: int, base: float, stream=None) -> None:
+    _check(lib.ts_rope(_ptr(q), _ptr(k), _ptr(v), q_stride, kv_stride, _ptr(pos), _ptr(seq_id), _ptr(cos_sin),
+                       table_len, _ptr(kcache), _ptr(vcache), T, nq, nkv, d, Lcap, base, _stream(stream)))
+
+
+def ts_rope_table(table_host: torch.Tensor, table_len: int, d: int, base: float) -> None:
+    """table_host: CPU float32 tensor [table_len, d], filled in place."""
+    assert not table_host.is_cuda and table_host.dtype == torch.float32 and table_host.numel() >= table_len * d
+    _check(lib.ts_rope_table(table_host.data_ptr(), table_len, d, base))
+
+
+def ts_attention_decode_workspace_bytes(B: int, nq: int, nkv: int, d: int, Lcap: int) -> int:
+    return lib.ts_attention_decode_workspace_bytes(B, nq, nkv, d, Lcap)
+
+
+def ts_attention_decode(q, kcache, vcache, seq_lens, out, B: int, nq: int, nkv: int, d: int, Lcap: int, scale: float,
+                        ws=None, stream=None) -> None:
+    _check(lib.ts_attention_decode(_ptr(q), _ptr(kcache), _ptr(vcache), _ptr(seq_lens), _ptr(out), B, nq, nkv, d, Lcap,
+                                   scale, _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def ts_attention_prefill(q, k, v, q_stride: int, kv_stride: int, cu_seqlens, out, S: int, T: int, max_seqlen: int,
+                         nq: int, nkv: int, d: int, scale: float, causal: bool = True, stream=None) -> None:
+    _check(lib.ts_attention_prefill(_ptr(q), _ptr(k), _ptr(v), q_stride, kv_stride, _ptr(cu_seqlens), _ptr(out), S, T,
+                                    max_seqlen, nq, nkv, d, scale, 1 if causal else 0, _stream(stream)))
+
+
+def ts_swiglu(gate_up, out, T: int, F: int, stream=None) -> None:
+    _check(lib.ts_swiglu(_ptr(gate_up), _ptr(out), T, F, _stream(stream)))
+
+
+def ts_moe_route(logits, T: int, E: int, k: int, topk_idx, topk_w, counts, offsets, perm, stream=None) -> None:
+    _check(lib.ts_moe_route(_ptr(logits), T, E, k, _ptr(topk_idx), _ptr(topk_w), _ptr(counts), _ptr(offsets),
+                            _ptr(perm), _stream(stream)))
+
+
+def ts_moe_gemm(A, row_map, row_div: int, W, offsets, Cout, rows: int, E: int, N: int, K: int, stream=None) -> None:
+    _check(lib.ts_moe_gemm(_ptr(A), _ptr(row_map), row_div, _ptr(W), _ptr(offsets), _ptr(Cout), rows, E, N, K,
+                           _stream(stream)))
+
+
+def ts_moe_combine(y, perm, topk_w, residual, out, scratch_inv, T: int, k: int, H: int, stream=None) -> None:
+    _check(lib.ts_moe_combine(_ptr(y), _ptr(perm), _ptr(topk_w), _ptr(residual), _ptr(out), _ptr(scratch_inv), T, k, H,
+                              _stream(stream)))
+
+
+# ---------------------------------------------------------------- layer / pipeline marshalling
+def make_desc(shape, Lcap: int, mode: str) -> LayerDesc:
+    return LayerDesc(H=shape.H, nq=shape.nq, nkv=shape.nkv, d=shape.d, F=shape.F, E=shape.E, k=shape.k, Lcap=Lcap,
+                     mode=TS_MODE_DECODE if mode == "decode" else TS_MODE_PREFILL, eps=shape.eps,
+                     rope_base=shape.rope_base)
+
+
+def make_weights(w: dict, rope_table=None) -> LayerWeights:
+    return LayerWeights(gamma1=_ptr(w["gamma1"]), w_qkv=_ptr(w["w_qkv"]), w_o=_ptr(w["w_o"]), gamma2=_ptr(w["gamma2"]),
+                        w_router=_ptr(w.get("w_router")), w_gate_up=_ptr(w["w_gate_up"]), w_down=_ptr(w["w_down"]),
+                        rope_cos_sin=_ptr(rope_table), rope_table_len=0 if rope_table is None else rope_table.shape[0])
+
+
+def make_io(io: dict, out, T: int, B: int, max_seqlen: int = 0) -> LayerIO:
+    return LayerIO(x=_ptr(io["x"]), out=_ptr(out), pos=_ptr(io["pos"]), seq_id=_ptr(io["seq_id"]),
+                   seq_lens=_ptr(io.get("seq_lens")), cu_seqlens=_ptr(io.get("cu_seqlens")), kcache=_ptr(io["kcache"]),
+                   vcache=_ptr(io["vcache"]), T=T, B=B, max_seqlen=max_seqlen)
+
+
+def ts_layer_workspace_bytes(desc: LayerDesc, T: int, B: int) -> int:
+    return lib.ts_layer_workspace_bytes(C.byref(desc), T, B)
+
+
+def ts_layer_boundary(desc: LayerDesc, T: int, B: int, index: int):
+    off, nb = _z(), _z()
+    _check(lib.ts_layer_boundary(C.byref(desc), T, B, index, C.byref(off), C.byref(nb)))
+    o = off.value
+    return (None if o == C.c_size_t(-1).value else o), nb.value
+
+
+def ts_layer_moe_buffers(desc: LayerDesc, T: int, B: int):
+    arr = (_z * 6)()
+    _check(lib.ts_layer_moe_buffers(C.byref(desc), T, B, arr))
+    return list(arr)
+
+
+def ts_layer_forward(desc: LayerDesc, weights: LayerWeights, io: LayerIO, ws, stream=None) -> None:
+    _check(lib.ts_layer_forward(C.byref(desc), C.byref(weights), C.byref(io), _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def ts_pipeline_create(desc: LayerDesc, max_micro_batches: int) -> int:
+    h = _p()
+    _check(lib.ts_pipeline_create(C.byref(desc), max_micro_batches, C.byref(h)))
+    return h.value
+
+
+def ts_pipeline_destroy(handle: int) -> None:
+    lib.ts_pipeline_destroy(handle)
+
+
+def ts_pipeline_boundary_layout(desc: LayerDesc, T: int, B: int, mask: int):
+    offs = (_z * (TS_NB_MOE + 1))()
+    n = _i()
+    _check(lib.ts_pipeline_boundary_layout(C.byref(desc), T, B, mask & (2 ** 64 - 1), offs, C.byref(n)))
+    return list(offs[: n.value + 1])
+
+
+def ts_pipeline_slot_stride(desc: LayerDesc, T: int, B: int, mask: int) -> int:
+    return lib.ts_pipeline_slot_stride(C.byref(desc), T, B, mask & (2 ** 64 - 1))
+
+
+def ts_pipeline_step(handle: int, weights: LayerWeights, mbs: Sequence[LayerIO], compute_streams, copy_stream,
+                     mask: int, dev_staging, pinned_host, ws, copy_on_compute_stream: bool = False) -> None:
+    arr = (LayerIO * len(mbs))(*mbs)
+    cs = (_p * 2)(_stream(compute_streams[0]), _stream(compute_streams[1]))
+    _check(lib.ts_pipeline_step(handle, C.byref(weights), arr, len(mbs), cs, _stream(copy_stream),
+                                mask & (2 ** 64 - 1), 1 if copy_on_compute_stream else 0, _ptr(dev_staging),
+                                _ptr(pinned_host), _nbytes(dev_staging), _ptr(ws), _nbytes(ws)))

@@ -1,0 +1,555 @@
+// C ABI: argument validation, workspace planning, the whole-layer call and the pipelined
+// micro-batch step.  Validation runs before the first HIP call so it can be exercised on a
+// host without a GPU.
+#include <cstdarg>
+#include <cstdio>
+#include <cmath>
+#include <new>
+#include <vector>
+
+#include "common.hpp"
+
+namespace ts {
+
+static thread_local char g_err[512] = "";
+
+void set_error(const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+}
+int fail(int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof(g_err), fmt, ap);
+  va_end(ap);
+  return code;
+}
+int check_hip(hipError_t e, const char* what) {
+  if (e == hipSuccess) return TS_OK;
+  snprintf(g_err, sizeof(g_err), "HIP error %d (%s) at %s", (int)e, hipGetErrorString(e), what);
+  return TS_ERR_HIP;
+}
+
+namespace {
+
+inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+// ---- layer workspace plan ---------------------------------------------------
+struct LayerPlan {
+  size_t h1, qkv, attn, x2, h2, gate_up, act, y;         // boundary buffers (byte offsets)
+  size_t logits, topk_idx, topk_w, counts, offsets, perm, inv;  // MoE routing buffers
+  size_t scratch, scratch_bytes;
+  size_t total;
+  size_t bytes[TS_NB_MOE];                               // size of each boundary
+};
+
+int validate_desc(const ts_layer_desc* d, const char* who) {
+  TS_REQUIRE(d != nullptr, TS_ERR_INVALID_ARG, "%s: null descriptor", who);
+  TS_REQUIRE(d->H > 0 && d->nq > 0 && d->nkv > 0 && d->d > 0 && d->F > 0 && d->Lcap > 0, TS_ERR_INVALID_ARG,
+             "%s: non-positive dimension", who);
+  TS_REQUIRE(d->nq % d->nkv == 0, TS_ERR_INVALID_ARG, "%s: nq %% nkv != 0", who);
+  TS_REQUIRE(d->mode == TS_MODE_DECODE || d->mode == TS_MODE_PREFILL, TS_ERR_INVALID_ARG, "%s: bad mode", who);
+  TS_REQUIRE(d->E >= 0 && (d->E == 0 || (d->k >= 1 && d->k <= d->E)), TS_ERR_INVALID_ARG, "%s: bad E/k", who);
+  TS_REQUIRE(d->H % 8 == 0 && d->H <= 32768 && d->F % 8 == 0, TS_ERR_UNSUPPORTED_SHAPE,
+             "%s: H and F must be multiples of 8, H <= 32768", who);
+  TS_REQUIRE(d->d == 64 || d->d == 128, TS_ERR_UNSUPPORTED_SHAPE, "%s: head dim must be 64 or 128", who);
+  TS_REQUIRE(d->nq / d->nkv <= 16, TS_ERR_UNSUPPORTED_SHAPE, "%s: GQA group larger than 16", who);
+  TS_REQUIRE(d->E <= 64, TS_ERR_UNSUPPORTED_SHAPE, "%s: more than 64 experts", who);
+  return TS_OK;
+}
+
+LayerPlan plan_layer(const ts_layer_desc& d, int T, int B) {
+  LayerPlan p{};
+  size_t off = 0;
+  auto take = [&](size_t bytes) {
+    size_t o = off;
+    off += round_up(bytes, 256);
+    return o;
+  };
+  const size_t nqkv = (size_t)(d.nq + 2 * d.nkv) * d.d;
+  const size_t rows = d.E > 0 ? (size_t)T * d.k : (size_t)T;
+  p.bytes[TS_B_H1] = (size_t)T * d.H * 2;
+  p.bytes[TS_B_QKV] = (size_t)T * nqkv * 2;
+  p.bytes[TS_B_ATTN] = (size_t)T * d.nq * d.d * 2;
+  p.bytes[TS_B_X2] = (size_t)T * d.H * 2;
+  p.bytes[TS_B_H2] = (size_t)T * d.H * 2;
+  p.bytes[TS_B_GATE_UP] = rows * 2 * d.F * 2;
+  p.bytes[TS_B_ACT] = rows * d.F * 2;
+  if (d.E > 0) {
+    p.bytes[TS_B_Y_MOE] = rows * d.H * 2;
+    p.bytes[TS_B_OUT_MOE] = (size_t)T * d.H * 2;
+  } else {
+    p.bytes[TS_B_OUT_DENSE] = (size_t)T * d.H * 2;
+  }
+  p.h1 = take(p.bytes[TS_B_H1]);
+  p.qkv = take(p.bytes[TS_B_QKV]);
+  p.attn = take(p.bytes[TS_B_ATTN]);
+  p.x2 = take(p.bytes[TS_B_X2]);
+  p.h2 = take(p.bytes[TS_B_H2]);
+  p.gate_up = take(p.bytes[TS_B_GATE_UP]);
+  p.act = take(p.bytes[TS_B_ACT]);
+  if (d.E > 0) {
+    p.y = take(p.bytes[TS_B_Y_MOE]);
+    p.logits = take((size_t)T * d.E * 4);
+    p.topk_idx = take((size_t)T * d.k * 4);
+    p.topk_w = take((size_t)T * d.k * 4);
+    p.counts = take((size_t)d.E * 4);
+    p.offsets = take((size_t)(d.E + 1) * 4);
+    p.perm = take((size_t)T * d.k * 4);
+    p.inv = take((size_t)T * d.k * 4);
+  }
+  size_t sc = 0;
+  auto mx = [&](size_t v) { if (v > sc) sc = v; };
+  mx(gemm_workspace_bytes(T, (int)nqkv, d.H));
+  mx(gemm_workspace_bytes(T, d.H, d.nq * d.d));
+  if (d.E > 0) {
+    mx(gemm_workspace_bytes(T, d.E, d.H));
+  } else {
+    mx(gemm_workspace_bytes(T, 2 * d.F, d.H));
+    mx(gemm_workspace_bytes(T, d.H, d.F));
+  }
+  if (d.mode == TS_MODE_DECODE) mx(attention_decode_workspace_bytes(B, d.nq, d.nkv, d.d, d.Lcap));
+  p.scratch_bytes = sc;
+  p.scratch = take(sc);
+  p.total = off;
+  return p;
+}
+
+size_t boundary_offset(const LayerPlan& p, const ts_layer_desc& d, int index) {
+  switch (index) {
+    case TS_B_H1: return p.h1;
+    case TS_B_QKV: return p.qkv;
+    case TS_B_ATTN: return p.attn;
+    case TS_B_X2: return p.x2;
+    case TS_B_H2: return p.h2;
+    case TS_B_GATE_UP: return p.gate_up;
+    case TS_B_ACT: return p.act;
+    default: break;
+  }
+  if (d.E > 0 && index == TS_B_Y_MOE) return p.y;
+  return (size_t)-1;  // the layer output lives in io->out
+}
+
+int validate_io(const ts_layer_desc* desc, const ts_layer_weights* w, const ts_layer_io* io, const char* who) {
+  TS_REQUIRE(w != nullptr && io != nullptr, TS_ERR_INVALID_ARG, "%s: null weights/io", who);
+  TS_REQUIRE(io->T >= 0 && io->B >= 0, TS_ERR_INVALID_ARG, "%s: negative T/B", who);
+  TS_REQUIRE(w->gamma1 && w->w_qkv && w->w_o && w->gamma2 && w->w_gate_up && w->w_down, TS_ERR_INVALID_ARG,
+             "%s: null weight pointer", who);
+  TS_REQUIRE(desc->E == 0 || w->w_router != nullptr, TS_ERR_INVALID_ARG, "%s: MoE layer without router", who);
+  TS_REQUIRE(io->x && io->out && io->pos && io->seq_id && io->kcache && io->vcache, TS_ERR_INVALID_ARG,
+             "%s: null io pointer", who);
+  TS_REQUIRE(aligned16(io->x) && aligned16(io->out) && aligned16(io->kcache) && aligned16(io->vcache), TS_ERR_INVALID_ARG,
+             "%s: io pointer not 16-byte aligned", who);
+  if (desc->mode == TS_MODE_DECODE) {
+    TS_REQUIRE(io->seq_lens != nullptr, TS_ERR_INVALID_ARG, "%s: decode needs seq_lens", who);
+    TS_REQUIRE(io->T == io->B, TS_ERR_INVALID_ARG, "%s: decode expects one token per sequence (T == B)", who);
+  } else {
+    TS_REQUIRE(io->cu_seqlens != nullptr && io->max_seqlen >= 0, TS_ERR_INVALID_ARG,
+               "%s: prefill needs cu_seqlens and max_seqlen", who);
+  }
+  return TS_OK;
+}
+
+// The layer, with a hook invoked right after each kernel boundary has been enqueued.
+template <typename Hook>
+int layer_forward_impl(const ts_layer_desc& d, const ts_layer_weights& w, const ts_layer_io& io, char* ws,
+                       hipStream_t s, Hook&& hook) {
+  const int T = io.T, B = io.B;
+  if (T == 0) return TS_OK;
+  const LayerPlan p = plan_layer(d, T, B);
+  const int nqd = d.nq * d.d, nkd = d.nkv * d.d, nqkv = nqd + 2 * nkd;
+  ts_bf16* h1 = reinterpret_cast<ts_bf16*>(ws + p.h1);
+  ts_bf16* qkv = reinterpret_cast<ts_bf16*>(ws + p.qkv);
+  ts_bf16* attn = reinterpret_cast<ts_bf16*>(ws + p.attn);
+  ts_bf16* x2 = reinterpret_cast<ts_bf16*>(ws + p.x2);
+  ts_bf16* h2 = reinterpret_cast<ts_bf16*>(ws + p.h2);
+  ts_bf16* gate_up = reinterpret_cast<ts_bf16*>(ws + p.gate_up);
+  ts_bf16* act = reinterpret_cast<ts_bf16*>(ws + p.act);
+  void* scratch = ws + p.scratch;
+  const float scale = 1.0f / sqrtf((float)d.d);
+  int rc;
+#define TS_STEP(call) do { rc = (call); if (rc != TS_OK) return rc; } while (0)
+  TS_STEP(launch_rmsnorm(io.x, w.gamma1, h1, T, d.H, d.eps, s));
+  TS_STEP(hook(TS_B_H1, h1));
+  TS_STEP(launch_gemm(h1, w.w_qkv, nullptr, qkv, false, T, nqkv, d.H, scratch, p.scratch_bytes, s));
+  TS_STEP(launch_rope(qkv, qkv + nqd, qkv + nqd + nkd, nqkv, nqkv, io.pos, io.seq_id, w.rope_cos_sin,
+                      w.rope_cos_sin ? w.rope_table_len : 0, io.kcache, io.vcache, T, d.nq, d.nkv, d.d, d.Lcap,
+                      d.rope_base, s));
+  TS_STEP(hook(TS_B_QKV, qkv));
+  if (d.mode == TS_MODE_DECODE) {
+    TS_STEP(launch_attention_decode(qkv, nqkv, io.kcache, io.vcache, io.seq_lens, attn, B, d.nq, d.nkv, d.d, d.Lcap,
+                                    scale, scratch, p.scratch_bytes, s));
+  } else {
+    TS_STEP(launch_attention_prefill(qkv, qkv + nqd, qkv + nqd + nkd, nqkv, nqkv, io.cu_seqlens, attn, B, T,
+                                     io.max_seqlen, d.nq, d.nkv, d.d, scale, 1, s));
+  }
+  TS_STEP(hook(TS_B_ATTN, attn));
+  TS_STEP(launch_gemm(attn, w.w_o, io.x, x2, false, T, d.H, nqd, scratch, p.scratch_bytes, s));
+  TS_STEP(hook(TS_B_X2, x2));
+  TS_STEP(launch_rmsnorm(x2, w.gamma2, h2, T, d.H, d.eps, s));
+  TS_STEP(hook(TS_B_H2, h2));
+  if (d.E == 0) {
+    TS_STEP(launch_gemm(h2, w.w_gate_up, nullptr, gate_up, false, T, 2 * d.F, d.H, scratch, p.scratch_bytes, s));
+    TS_STEP(hook(TS_B_GATE_UP, gate_up));
+    TS_STEP(launch_swiglu(gate_up, act, T, d.F, s));
+    TS_STEP(hook(TS_B_ACT, act));
+    TS_STEP(launch_gemm(act, w.w_down, x2, io.out, false, T, d.H, d.F, scratch, p.scratch_bytes, s));
+    TS_STEP(hook(TS_B_OUT_DENSE, io.out));
+  } else {
+    float* logits = reinterpret_cast<float*>(ws + p.logits);
+    int32_t* tidx = reinterpret_cast<int32_t*>(ws + p.topk_idx);
+    float* tw = reinterpret_cast<float*>(ws + p.topk_w);
+    int32_t* counts = reinterpret_cast<int32_t*>(ws + p.counts);
+    int32_t* offs = reinterpret_cast<int32_t*>(ws + p.offsets);
+    int32_t* perm = reinterpret_cast<int32_t*>(ws + p.perm);
+    int32_t* inv = reinterpret_cast<int32_t*>(ws + p.inv);
+    ts_bf16* y = reinterpret_cast<ts_bf16*>(ws + p.y);
+    const int rows = T * d.k;
+    TS_STEP(launch_gemm(h2, w.w_router, nullptr, logits, true, T, d.E, d.H, scratch, p.scratch_bytes, s));
+    TS_STEP(launch_moe_route(logits, T, d.E, d.k, tidx, tw, counts, offs, perm, s));
+    TS_STEP(launch_moe_gemm(h2, perm, d.k, w.w_gate_up, offs, gate_up, rows, d.E, 2 * d.F, d.H, s));
+    TS_STEP(hook(TS_B_GATE_UP, gate_up));
+    TS_STEP(launch_swiglu(gate_up, act, rows, d.F, s));
+    TS_STEP(hook(TS_B_ACT, act));
+    TS_STEP(launch_moe_gemm(act, nullptr, 1, w.w_down, offs, y, rows, d.E, d.H, d.F, s));
+    TS_STEP(hook(TS_B_Y_MOE, y));
+    TS_STEP(launch_moe_combine(y, perm, tw, x2, io.out, inv, T, d.k, d.H, s));
+    TS_STEP(hook(TS_B_OUT_MOE, io.out));
+  }
+#undef TS_STEP
+  return TS_OK;
+}
+
+}  // namespace
+}  // namespace ts
+
+using namespace ts;
+
+extern "C" {
+
+const char* ts_strerror(int code) {
+  switch (code) {
+    case TS_OK: return "ok";
+    case TS_ERR_INVALID_ARG: return "invalid argument";
+    case TS_ERR_UNSUPPORTED_SHAPE: return "unsupported shape";
+    case TS_ERR_WORKSPACE: return "workspace too small";
+    case TS_ERR_HIP: return "HIP runtime error";
+    default: return "unknown error";
+  }
+}
+const char* ts_last_error(void) { return g_err; }
+const char* ts_version(void) { return "tessera-mi355x 0.1 (gfx950)"; }
+
+int ts_rmsnorm(const ts_bf16* x, const ts_bf16* gamma, ts_bf16* y, int T, int H, float eps, void* stream) {
+  TS_REQUIRE(T >= 0 && H > 0, TS_ERR_INVALID_ARG, "ts_rmsnorm: T=%d H=%d", T, H);
+  TS_REQUIRE(T == 0 || (x && gamma && y), TS_ERR_INVALID_ARG, "ts_rmsnorm: null pointer");
+  TS_REQUIRE(aligned16(x) && aligned16(gamma) && aligned16(y), TS_ERR_INVALID_ARG, "ts_rmsnorm: pointer not 16-byte aligned");
+  TS_REQUIRE(H % 8 == 0 && H <= 32768, TS_ERR_UNSUPPORTED_SHAPE, "ts_rmsnorm: H=%d must be a multiple of 8 and <= 32768", H);
+  return launch_rmsnorm(x, gamma, y, T, H, eps, as_stream(stream));
+}
+
+static int check_gemm(const char* who, const void* A, const void* W, const void* C, int M, int N, int K) {
+  TS_REQUIRE(M >= 0 && N > 0 && K > 0, TS_ERR_INVALID_ARG, "%s: M=%d N=%d K=%d", who, M, N, K);
+  TS_REQUIRE(M == 0 || (A && W && C), TS_ERR_INVALID_ARG, "%s: null pointer", who);
+  TS_REQUIRE(aligned16(A) && aligned16(W) && aligned16(C), TS_ERR_INVALID_ARG, "%s: pointer not 16-byte aligned", who);
+  TS_REQUIRE(K % 8 == 0 && N % 2 == 0, TS_ERR_UNSUPPORTED_SHAPE, "%s: K=%d must be a multiple of 8 and N=%d even", who, K, N);
+  return TS_OK;
+}
+
+size_t ts_gemm_workspace_bytes(int M, int N, int K) { return gemm_workspace_bytes(M, N, K); }
+
+int ts_gemm_bf16(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, ts_bf16* C, int M, int N, int K,
+                 void* ws, size_t ws_bytes, void* stream) {
+  int rc = check_gemm("ts_gemm_bf16", A, W, C, M, N, K);
+  if (rc != TS_OK) return rc;
+  TS_REQUIRE(aligned16(residual) && aligned16(ws), TS_ERR_INVALID_ARG, "ts_gemm_bf16: pointer not 16-byte aligned");
+  return launch_gemm(A, W, residual, C, false, M, N, K, ws, ws_bytes, as_stream(stream));
+}
+
+int ts_gemm_bf16_f32out(const ts_bf16* A, const ts_bf16* W, float* C, int M, int N, int K, void* ws, size_t ws_bytes,
+                        void* stream) {
+  int rc = check_gemm("ts_gemm_bf16_f32out", A, W, C, M, N, K);
+  if (rc != TS_OK) return rc;
+  TS_REQUIRE(aligned16(ws), TS_ERR_INVALID_ARG, "ts_gemm_bf16_f32out: pointer not 16-byte aligned");
+  return launch_gemm(A, W, nullptr, C, true, M, N, K, ws, ws_bytes, as_stream(stream));
+}
+
+int ts_rope(ts_bf16* q, ts_bf16* k, const ts_bf16* v, int q_stride, int kv_stride, const int32_t* pos,
+            const int32_t* seq_id, const float* cos_sin, int table_len, ts_bf16* kcache, ts_bf16* vcache, int T, int nq,
+            int nkv, int d, int Lcap, float base, void* stream) {
+  TS_REQUIRE(T >= 0 && nq > 0 && nkv > 0 && d > 0, TS_ERR_INVALID_ARG, "ts_rope: T=%d nq=%d nkv=%d d=%d", T, nq, nkv, d);
+  TS_REQUIRE(T == 0 || (q && k && pos), TS_ERR_INVALID_ARG, "ts_rope: null pointer");
+  TS_REQUIRE((kcache == nullptr) == (vcache == nullptr), TS_ERR_INVALID_ARG, "ts_rope: kcache and vcache must both be set or both NULL");
+  TS_REQUIRE(kcache == nullptr || (v && seq_id && Lcap > 0), TS_ERR_INVALID_ARG, "ts_rope: append needs v, seq_id and Lcap > 0");
+  TS_REQUIRE(cos_sin == nullptr || table_len > 0, TS_ERR_INVALID_ARG, "ts_rope: table without length");
+  TS_REQUIRE(base > 0.f, TS_ERR_INVALID_ARG, "ts_rope: base must be positive");
+  TS_REQUIRE(aligned16(q) && aligned16(k) && aligned16(v) && aligned16(cos_sin) && aligned16(kcache) && aligned16(vcache),
+             TS_ERR_INVALID_ARG, "ts_rope: pointer not 16-byte aligned");
+  TS_REQUIRE(d % 16 == 0 && d <= 256, TS_ERR_UNSUPPORTED_SHAPE, "ts_rope: d=%d must be a multiple of 16 and <= 256", d);
+  TS_REQUIRE(q_stride % 8 == 0 && kv_stride % 8 == 0 && q_stride >= nq * d && kv_stride >= nkv * d,
+             TS_ERR_UNSUPPORTED_SHAPE, "ts_rope: bad strides %d/%d", q_stride, kv_stride);
+  return launch_rope(q, k, v, q_stride, kv_stride, pos, seq_id, cos_sin, cos_sin ? table_len : 0, kcache, vcache, T, nq,
+                     nkv, d, Lcap, base, as_stream(stream));
+}
+
+int ts_rope_table(float* table_host, int table_len, int d, float base) {
+  TS_REQUIRE(table_host != nullptr && table_len > 0 && d > 0 && d % 2 == 0 && base > 0.f, TS_ERR_INVALID_ARG,
+             "ts_rope_table: bad arguments");
+  const int half = d / 2;
+  for (int p = 0; p < table_len; ++p) {
+    float* row = table_host + (size_t)p * d;
+    for (int i = 0; i < half; ++i) {
+      const double theta = std::pow((double)base, -2.0 * (double)i / (double)d);
+      const double ang = (double)p * theta;
+      row[i] = (float)std::cos(ang);
+      row[half + i] = (float)std::sin(ang);
+    }
+  }
+  return TS_OK;
+}
+
+size_t ts_attention_decode_workspace_bytes(int B, int nq, int nkv, int d, int Lcap) {
+  return attention_decode_workspace_bytes(B, nq, nkv, d, Lcap);
+}
+
+int ts_attention_decode(const ts_bf16* q, const ts_bf16* kcache, const ts_bf16* vcache, const int32_t* seq_lens,
+                        ts_bf16* out, int B, int nq, int nkv, int d, int Lcap, float scale, void* ws, size_t ws_bytes,
+                        void* stream) {
+  TS_REQUIRE(B >= 0 && nq > 0 && nkv > 0 && d > 0 && Lcap > 0, TS_ERR_INVALID_ARG,
+             "ts_attention_decode: B=%d nq=%d nkv=%d d=%d Lcap=%d", B, nq, nkv, d, Lcap);
+  TS_REQUIRE(nq % nkv == 0, TS_ERR_INVALID_ARG, "ts_attention_decode: nq %% nkv != 0");
+  TS_REQUIRE(B == 0 || (q && kcache && vcache && seq_lens && out), TS_ERR_INVALID_ARG, "ts_attention_decode: null pointer");
+  TS_REQUIRE(aligned16(q) && aligned16(kcache) && aligned16(vcache) && aligned16(out) && aligned16(ws), TS_ERR_INVALID_ARG,
+             "ts_attention_decode: pointer not 16-byte aligned");
+  TS_REQUIRE(d == 64 || d == 128, TS_ERR_UNSUPPORTED_SHAPE, "ts_attention_decode: d=%d (64 or 128 supported)", d);
+  TS_REQUIRE(nq / nkv <= 16, TS_ERR_UNSUPPORTED_SHAPE, "ts_attention_decode: GQA group %d > 16", nq / nkv);
+  return launch_attention_decode(q, nq * d, kcache, vcache, seq_lens, out, B, nq, nkv, d, Lcap, scale, ws, ws_bytes,
+                                 as_stream(stream));
+}
+
+int ts_attention_prefill(const ts_bf16* q, const ts_bf16* k, const ts_bf16* v, int q_stride, int kv_stride,
+                         const int32_t* cu_seqlens, ts_bf16* out, int S, int T, int max_seqlen, int nq, int nkv, int d,
+                         float scale, int causal, void* stream) {
+  TS_REQUIRE(S >= 0 && T >= 0 && max_seqlen >= 0 && nq > 0 && nkv > 0 && d > 0, TS_ERR_INVALID_ARG,
+             "ts_attention_prefill: S=%d T=%d nq=%d nkv=%d d=%d", S, T, nq, nkv, d);
+  TS_REQUIRE(nq % nkv == 0, TS_ERR_INVALID_ARG, "ts_attention_prefill: nq %% nkv != 0");
+  TS_REQUIRE(S == 0 || T == 0 || (q && k && v && cu_seqlens && out), TS_ERR_INVALID_ARG, "ts_attention_prefill: null pointer");
+  TS_REQUIRE(aligned16(q) && aligned16(k) && aligned16(v) && aligned16(out), TS_ERR_INVALID_ARG,
+             "ts_attention_prefill: pointer not 16-byte aligned");
+  TS_REQUIRE(d == 64 || d == 128, TS_ERR_UNSUPPORTED_SHAPE, "ts_attention_prefill: d=%d (64 or 128 supported)", d);
+  TS_REQUIRE(q_stride % 8 == 0 && kv_stride % 8 == 0 && q_stride >= nq * d && kv_stride >= nkv * d,
+             TS_ERR_UNSUPPORTED_SHAPE, "ts_attention_prefill: bad strides %d/%d", q_stride, kv_stride);
+  return launch_attention_prefill(q, k, v, q_stride, kv_stride, cu_seqlens, out, S, T, max_seqlen, nq, nkv, d, scale,
+                                  causal, as_stream(stream));
+}
+
+int ts_swiglu(const ts_bf16* gate_up, ts_bf16* out, int T, int F, void* stream) {
+  TS_REQUIRE(T >= 0 && F > 0, TS_ERR_INVALID_ARG, "ts_swiglu: T=%d F=%d", T, F);
+  TS_REQUIRE(T == 0 || (gate_up && out), TS_ERR_INVALID_ARG, "ts_swiglu: null pointer");
+  TS_REQUIRE(aligned16(gate_up) && aligned16(out), TS_ERR_INVALID_ARG, "ts_swiglu: pointer not 16-byte aligned");
+  TS_REQUIRE(F % 8 == 0, TS_ERR_UNSUPPORTED_SHAPE, "ts_swiglu: F=%d must be a multiple of 8", F);
+  return launch_swiglu(gate_up, out, T, F, as_stream(stream));
+}
+
+int ts_moe_route(const float* logits, int T, int E, int k, int32_t* topk_idx, float* topk_w, int32_t* counts,
+                 int32_t* offsets, int32_t* perm, void* stream) {
+  TS_REQUIRE(T >= 0 && E > 0 && k >= 1 && k <= E, TS_ERR_INVALID_ARG, "ts_moe_route: T=%d E=%d k=%d", T, E, k);
+  TS_REQUIRE(counts && offsets && (T == 0 || (logits && topk_idx && topk_w && perm)), TS_ERR_INVALID_ARG,
+             "ts_moe_route: null pointer");
+  TS_REQUIRE(E <= 64 && (long)T * k <= (1L << 20), TS_ERR_UNSUPPORTED_SHAPE, "ts_moe_route: E <= 64 and T*k <= 2^20 required");
+  return launch_moe_route(logits, T, E, k, topk_idx, topk_w, counts, offsets, perm, as_stream(stream));
+}
+
+int ts_moe_gemm(const ts_bf16* A, const int32_t* row_map, int row_div, const ts_bf16* W, const int32_t* offsets,
+                ts_bf16* C, int rows, int E, int N, int K, void* stream) {
+  TS_REQUIRE(rows >= 0 && E > 0 && N > 0 && K > 0, TS_ERR_INVALID_ARG, "ts_moe_gemm: rows=%d E=%d N=%d K=%d", rows, E, N, K);
+  TS_REQUIRE(rows == 0 || (A && W && offsets && C), TS_ERR_INVALID_ARG, "ts_moe_gemm: null pointer");
+  TS_REQUIRE(row_map == nullptr || row_div >= 1, TS_ERR_INVALID_ARG, "ts_moe_gemm: row_div must be >= 1");
+  TS_REQUIRE(aligned16(A) && aligned16(W) && aligned16(C), TS_ERR_INVALID_ARG, "ts_moe_gemm: pointer not 16-byte aligned");
+  TS_REQUIRE(K % 8 == 0 && N % 2 == 0, TS_ERR_UNSUPPORTED_SHAPE, "ts_moe_gemm: K=%d must be a multiple of 8 and N=%d even", K, N);
+  return launch_moe_gemm(A, row_map, row_map ? row_div : 1, W, offsets, C, rows, E, N, K, as_stream(stream));
+}
+
+int ts_moe_combine(const ts_bf16* y, const int32_t* perm, const float* topk_w, const ts_bf16* residual, ts_bf16* out,
+                   int32_t* scratch_inv, int T, int k, int H, void* stream) {
+  TS_REQUIRE(T >= 0 && k >= 1 && H > 0, TS_ERR_INVALID_ARG, "ts_moe_combine: T=%d k=%d H=%d", T, k, H);
+  TS_REQUIRE(T == 0 || (y && perm && topk_w && out && scratch_inv), TS_ERR_INVALID_ARG, "ts_moe_combine: null pointer");
+  TS_REQUIRE(aligned16(y) && aligned16(residual) && aligned16(out), TS_ERR_INVALID_ARG, "ts_moe_combine: pointer not 16-byte aligned");
+  TS_REQUIRE(H % 8 == 0, TS_ERR_UNSUPPORTED_SHAPE, "ts_moe_combine: H=%d must be a multiple of 8", H);
+  return launch_moe_combine(y, perm, topk_w, residual, out, scratch_inv, T, k, H, as_stream(stream));
+}
+
+// ---------------------------------------------------------------- layer
+size_t ts_layer_workspace_bytes(const ts_layer_desc* desc, int T, int B) {
+  if (validate_desc(desc, "ts_layer_workspace_bytes") != TS_OK || T < 0 || B < 0) return 0;
+  return plan_layer(*desc, T, B).total;
+}
+
+int ts_layer_boundary(const ts_layer_desc* desc, int T, int B, int index, size_t* ws_offset, size_t* bytes) {
+  int rc = validate_desc(desc, "ts_layer_boundary");
+  if (rc != TS_OK) return rc;
+  const int nb = desc->E > 0 ? TS_NB_MOE : TS_NB_DENSE;
+  TS_REQUIRE(T >= 0 && B >= 0 && index >= 0 && index < nb && ws_offset && bytes, TS_ERR_INVALID_ARG,
+             "ts_layer_boundary: bad index %d", index);
+  LayerPlan p = plan_layer(*desc, T, B);
+  *ws_offset = boundary_offset(p, *desc, index);
+  *bytes = p.bytes[index];
+  return TS_OK;
+}
+
+int ts_layer_moe_buffers(const ts_layer_desc* desc, int T, int B, size_t ws_offsets[6]) {
+  int rc = validate_desc(desc, "ts_layer_moe_buffers");
+  if (rc != TS_OK) return rc;
+  TS_REQUIRE(desc->E > 0 && ws_offsets && T >= 0 && B >= 0, TS_ERR_INVALID_ARG, "ts_layer_moe_buffers: not a MoE layer");
+  LayerPlan p = plan_layer(*desc, T, B);
+  ws_offsets[0] = p.logits; ws_offsets[1] = p.topk_idx; ws_offsets[2] = p.topk_w;
+  ws_offsets[3] = p.counts; ws_offsets[4] = p.offsets; ws_offsets[5] = p.perm;
+  return TS_OK;
+}
+
+int ts_layer_forward(const ts_layer_desc* desc, const ts_layer_weights* w, const ts_layer_io* io, void* ws,
+                     size_t ws_bytes, void* stream) {
+  int rc = validate_desc(desc, "ts_layer_forward");
+  if (rc != TS_OK) return rc;
+  rc = validate_io(desc, w, io, "ts_layer_forward");
+  if (rc != TS_OK) return rc;
+  const size_t need = plan_layer(*desc, io->T, io->B).total;
+  TS_REQUIRE(io->T == 0 || (ws != nullptr && ws_bytes >= need), TS_ERR_WORKSPACE,
+             "ts_layer_forward: workspace %zu bytes < required %zu", ws_bytes, need);
+  TS_REQUIRE(aligned16(ws), TS_ERR_INVALID_ARG, "ts_layer_forward: workspace not 16-byte aligned");
+  return layer_forward_impl(*desc, *w, *io, reinterpret_cast<char*>(ws), as_stream(stream),
+                            [](int, const void*) { return TS_OK; });
+}
+
+// ---------------------------------------------------------------- pipeline
+struct ts_pipeline {
+  ts_layer_desc desc;
+  int max_mb;
+  std::vector<hipEvent_t> boundary_ev;  // [max_mb][TS_NB_MOE]
+  std::vector<hipEvent_t> packed_ev;    // [max_mb]
+};
+
+int ts_pipeline_create(const ts_layer_desc* desc, int max_micro_batches, ts_pipeline** out) {
+  int rc = validate_desc(desc, "ts_pipeline_create");
+  if (rc != TS_OK) return rc;
+  TS_REQUIRE(out != nullptr && max_micro_batches > 0 && max_micro_batches <= 64, TS_ERR_INVALID_ARG,
+             "ts_pipeline_create: bad arguments");
+  ts_pipeline* p = new (std::nothrow) ts_pipeline();
+  TS_REQUIRE(p != nullptr, TS_ERR_INVALID_ARG, "ts_pipeline_create: out of host memory");
+  p->desc = *desc;
+  p->max_mb = max_micro_batches;
+  const int n = max_micro_batches * TS_NB_MOE + max_micro_batches;
+  for (int i = 0; i < n; ++i) {
+    hipEvent_t e;
+    hipError_t err = hipEventCreateWithFlags(&e, hipEventDisableTiming);
+    if (err != hipSuccess) {
+      ts_pipeline_destroy(p);
+      return check_hip(err, "hipEventCreateWithFlags");
+    }
+    if (i < max_micro_batches * TS_NB_MOE) p->boundary_ev.push_back(e);
+    else p->packed_ev.push_back(e);
+  }
+  *out = p;
+  return TS_OK;
+}
+
+void ts_pipeline_destroy(ts_pipeline* p) {
+  if (p == nullptr) return;
+  for (hipEvent_t e : p->boundary_ev) (void)hipEventDestroy(e);
+  for (hipEvent_t e : p->packed_ev) (void)hipEventDestroy(e);
+  delete p;
+}
+
+int ts_pipeline_boundary_layout(const ts_layer_desc* desc, int T, int B, uint64_t boundary_mask, size_t* offsets,
+                                int* n_boundaries) {
+  int rc = validate_desc(desc, "ts_pipeline_boundary_layout");
+  if (rc != TS_OK) return rc;
+  TS_REQUIRE(offsets && n_boundaries && T >= 0 && B >= 0, TS_ERR_INVALID_ARG, "ts_pipeline_boundary_layout: bad arguments");
+  const int nb = desc->E > 0 ? TS_NB_MOE : TS_NB_DENSE;
+  LayerPlan p = plan_layer(*desc, T, B);
+  size_t off = 0;
+  int n = 0;
+  for (int i = 0; i < nb; ++i) {
+    if (!((boundary_mask >> i) & 1)) continue;
+    offsets[n++] = off;
+    off += round_up(p.bytes[i], 16);
+  }
+  offsets[n] = off;
+  *n_boundaries = n;
+  return TS_OK;
+}
+
+size_t ts_pipeline_slot_stride(const ts_layer_desc* desc, int T, int B, uint64_t boundary_mask) {
+  size_t offs[TS_NB_MOE + 1];
+  int n = 0;
+  if (ts_pipeline_boundary_layout(desc, T, B, boundary_mask, offs, &n) != TS_OK) return 0;
+  return round_up(offs[n], 256);
+}
+
+int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_io* mb, int n_mb,
+                     void* compute_streams[2], void* copy_stream, uint64_t boundary_mask, int copy_on_compute_stream,
+                     void* dev_staging, void* pinned_host, size_t staging_bytes, void* ws, size_t ws_bytes) {
+  TS_REQUIRE(p != nullptr && w != nullptr && mb != nullptr && compute_streams != nullptr, TS_ERR_INVALID_ARG,
+             "ts_pipeline_step: null argument");
+  TS_REQUIRE(n_mb >= 1 && n_mb <= p->max_mb, TS_ERR_INVALID_ARG, "ts_pipeline_step: n_mb=%d outside [1,%d]", n_mb, p->max_mb);
+  const ts_layer_desc& d = p->desc;
+  const int nb = d.E > 0 ? TS_NB_MOE : TS_NB_DENSE;
+  if (nb < 64) boundary_mask &= ((1ull << nb) - 1ull);
+  int Tmax = 0, Bmax = 0;
+  for (int i = 0; i < n_mb; ++i) {
+    int rc = validate_io(&d, w, &mb[i], "ts_pipeline_step");
+    if (rc != TS_OK) return rc;
+    if (mb[i].T > Tmax) Tmax = mb[i].T;
+    if (mb[i].B > Bmax) Bmax = mb[i].B;
+  }
+  const size_t half = round_up(plan_layer(d, Tmax, Bmax).total, 256);
+  TS_REQUIRE(ws != nullptr && ws_bytes >= 2 * half, TS_ERR_WORKSPACE, "ts_pipeline_step: workspace %zu bytes < required %zu",
+             ws_bytes, 2 * half);
+  const size_t stride = ts_pipeline_slot_stride(&d, Tmax, Bmax, boundary_mask);
+  TS_REQUIRE(boundary_mask == 0 || (dev_staging && pinned_host && staging_bytes >= stride * (size_t)n_mb),
+             TS_ERR_WORKSPACE, "ts_pipeline_step: staging %zu bytes < required %zu", staging_bytes, stride * (size_t)n_mb);
+  TS_REQUIRE(aligned16(ws) && aligned16(dev_staging) && aligned16(pinned_host), TS_ERR_INVALID_ARG,
+             "ts_pipeline_step: buffer not 16-byte aligned");
+  hipStream_t cs[2] = {as_stream(compute_streams[0]), as_stream(compute_streams[1])};
+  hipStream_t copy = as_stream(copy_stream);
+
+  for (int i = 0; i < n_mb; ++i) {
+    hipStream_t s = cs[i & 1];
+    char* wsh = reinterpret_cast<char*>(ws) + (size_t)(i & 1) * half;
+    // the workspace half is reused by every second micro-batch: wait until its boundary
+    // tensors have been packed before overwriting them
+    if (i >= 2 && boundary_mask != 0 && !copy_on_compute_stream) TS_HIP(hipStreamWaitEvent(s, p->packed_ev[i - 2], 0));
+    const LayerPlan plan = plan_layer(d, mb[i].T, mb[i].B);
+    size_t offs[TS_NB_MOE + 1];
+    int n = 0;
+    int rc = ts_pipeline_boundary_layout(&d, mb[i].T, mb[i].B, boundary_mask, offs, &n);
+    if (rc != TS_OK) return rc;
+    char* slot_dev = reinterpret_cast<char*>(dev_staging) + (size_t)i * stride;
+    char* slot_host = reinterpret_cast<char*>(pinned_host) + (size_t)i * stride;
+    int ordinal = 0;
+    auto hook = [&](int index, const void* ptr) -> int {
+      if (!((boundary_mask >> index) & 1)) return TS_OK;
+      const size_t bytes = round_up(plan.bytes[index], 16);
+      const size_t o = offs[ordinal++];
+      hipStream_t target = s;
+      if (!copy_on_compute_stream) {
+        hipEvent_t e = p->boundary_ev[(size_t)i * TS_NB_MOE + index];
+        TS_HIP(hipEventRecord(e, s));
+        TS_HIP(hipStreamWaitEvent(copy, e, 0));
+        target = copy;
+      }
+      int r = launch_copy16(ptr, slot_dev + o, bytes, target);
+      if (r != TS_OK) return r;
+      TS_HIP(hipMemcpyAsync(slot_host + o, slot_dev + o, bytes, hipMemcpyDeviceToHost, target));
+      return TS_OK;
+    };
+    rc = layer_forward_impl(d, *w, mb[i], wsh, s, hook);
+    if (rc != TS_OK) return rc;
+    if (boundary_mask != 0 && !copy_on_compute_stream) TS_HIP(hipEventRecord(p->packed_ev[i], copy));
+  }
+  return TS_OK;
+}
+
+}  // extern "C"

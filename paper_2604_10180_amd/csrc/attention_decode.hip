@@ -1,0 +1,264 @@
+// Decode attention over the contiguous KV cache: the big bandwidth-bound kernel of a decode
+// iteration.  K and V are streamed once from HBM with 16-byte loads; all contractions run on
+// the matrix cores so the vector ALU only does the softmax bookkeeping:
+//
+//   S^T[key, head]  = K[key, :] . Q[head, :]      MFMA 16x16x32, A = K rows straight from global
+//   O^T[dcol, head] += V^T[dcol, key] P^T[key, head]  MFMA 16x16x32, A = V^T gathered from LDS
+//
+// The query heads of one kv head (GQA group, <= 16) fill the N dimension.  With this
+// orientation every lane owns one head column for scores, running max, running sum and
+// output accumulators, so the online-softmax state needs no cross-lane traffic except a
+// 2-step max over the four lane groups.
+//
+// Split-KV: grid (chunk, kv head, sequence); each workgroup reduces its chunk to an
+// un-normalised (m, l, O) triple per head in fp32; a second kernel merges the chunks.
+#include "common.hpp"
+
+namespace ts {
+
+namespace {
+constexpr int kBlockKeys = 32;   // keys per wave iteration
+constexpr int kMinChunk = 256;   // a sequence is split only into chunks of at least this many keys
+}
+
+__device__ __forceinline__ int decode_nchunk(int len, int NCH) {
+  int n = (len + kMinChunk - 1) / kMinChunk;
+  n = n < 1 ? 1 : n;
+  return n < NCH ? n : NCH;
+}
+
+template <int D>
+__global__ __launch_bounds__(256) void attn_decode_split_kernel(const ts_bf16* __restrict__ q,
+                                                                const ts_bf16* __restrict__ kc,
+                                                                const ts_bf16* __restrict__ vc,
+                                                                const int32_t* __restrict__ seq_lens,
+                                                                float* __restrict__ part, int q_stride, int nq, int nkv,
+                                                                int Lcap, int NCH, float c_scale /* scale * log2(e) */) {
+  constexpr int KSTEPS = D / 32;   // MFMA k-steps for Q.K
+  constexpr int DT = D / 16;       // 16-wide output column tiles
+  constexpr int CPR = D / 8;       // 16-byte chunks per cache row
+  constexpr int VROW = CPR + 1;    // uint4 per staged V row (one pad chunk: conflict-free gathers)
+  constexpr int VLOADS = kBlockKeys * CPR / 64;
+  constexpr int VROW_H = VROW * 8; // staged row stride in 16-bit elements
+
+  const int ch = blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, gq = lane >> 4;
+  const int g = nq / nkv;
+  const int len = seq_lens[b];
+  if (len <= 0) return;
+  const int nchunk = decode_nchunk(len, NCH);
+  if (ch >= nchunk) return;
+  const int clen = (len + nchunk - 1) / nchunk;
+  const int start = ch * clen;
+  const int end = min(len, start + clen);
+
+  extern __shared__ uint4 smem[];
+  uint4* vst = smem + (size_t)wave * kBlockKeys * VROW;                  // this wave's V stage
+  const uint16_t* vst_h = reinterpret_cast<const uint16_t*>(vst);
+
+  // Q fragments (B operand): lane (head l16, group gq) holds chunk j*4+gq of its head.
+  U4 qf[KSTEPS];
+  {
+    const ts_bf16* qrow = q + (size_t)b * q_stride + ((size_t)kvh * g + l16) * D;
+#pragma unroll
+    for (int j = 0; j < KSTEPS; ++j) qf[j].u = (l16 < g) ? ldg16(qrow + (j * 4 + gq) * 8) : make_uint4(0, 0, 0, 0);
+  }
+  const ts_bf16* kbase = kc + ((size_t)b * nkv + kvh) * (size_t)Lcap * D;
+  const ts_bf16* vbase = vc + ((size_t)b * nkv + kvh) * (size_t)Lcap * D;
+
+  float m_run = -INFINITY, l_run = 0.f;
+  f32x4 o[DT];
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) o[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int nblk = (end > start) ? (end - start + kBlockKeys - 1) / kBlockKeys : 0;
+  U4 kf[2][KSTEPS], vf[VLOADS];
+  auto load_block = [&](int blk) {
+    const int k0 = start + blk * kBlockKeys;
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+      const int key = min(k0 + kt * 16 + l16, end - 1);
+#pragma unroll
+      for (int j = 0; j < KSTEPS; ++j) kf[kt][j].u = ldg16(kbase + (size_t)key * D + (j * 4 + gq) * 8);
+    }
+#pragma unroll
+    for (int i = 0; i < VLOADS; ++i) {
+      const int c = lane + 64 * i;
+      const int key = min(k0 + c / CPR, end - 1);
+      vf[i].u = ldg16(vbase + (size_t)key * D + (c % CPR) * 8);
+    }
+  };
+
+  if (wave < nblk) load_block(wave);
+  for (int blk = wave; blk < nblk; blk += 4) {
+    const int k0 = start + blk * kBlockKeys;
+    // stage V (coalesced rows) and run the score MFMAs on the K fragments
+#pragma unroll
+    for (int i = 0; i < VLOADS; ++i) {
+      const int c = lane + 64 * i;
+      vst[(c / CPR) * VROW + (c % CPR)] = vf[i].u;
+    }
+    f32x4 s[2];
+#pragma unroll
+    for (int kt = 0; kt < 2; ++kt) {
+      s[kt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+      for (int j = 0; j < KSTEPS; ++j)
+        s[kt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[kt][j].b, qf[j].b, s[kt], 0, 0, 0);
+    }
+    if (blk + 4 < nblk) load_block(blk + 4);   // registers are free again: prefetch the next block
+
+    // s[kt][i] = S^T[key k0 + kt*16 + gq*4 + i][head l16]
+    float sv[8];
+    float bm = -INFINITY;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      const int key = k0 + (t >> 2) * 16 + gq * 4 + (t & 3);
+      sv[t] = (key < end) ? s[t >> 2][t & 3] * c_scale : -INFINITY;
+      bm = fmaxf(bm, sv[t]);
+    }
+    bm = fmaxf(bm, __shfl_xor(bm, 16, 64));
+    bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
+    const float m_new = fmaxf(m_run, bm);        // finite: the block's first key is valid
+    const float alpha = exp2f(m_run - m_new);    // 0 on the first block
+    float ps = 0.f;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+      sv[t] = exp2f(sv[t] - m_new);
+      ps += sv[t];
+    }
+    l_run = l_run * alpha + ps;
+    m_run = m_new;
+    U4 pf;
+#pragma unroll
+    for (int t = 0; t < 4; ++t) pf.w[t] = pack_bf16(sv[2 * t], sv[2 * t + 1]);
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
+
+    __builtin_amdgcn_wave_barrier();
+    // V^T fragments: lane (dcol dt*16+l16, group gq), k-slot t <-> key (t/4)*16 + gq*4 + t%4
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      U4 vt;
+#pragma unroll
+      for (int t = 0; t < 8; t += 2) {
+        const int key0 = (t >> 2) * 16 + gq * 4 + (t & 3);
+        uint32_t lo = vst_h[key0 * VROW_H + dt * 16 + l16];
+        uint32_t hi = vst_h[(key0 + 1) * VROW_H + dt * 16 + l16];
+        vt.w[t >> 1] = lo | (hi << 16);
+      }
+      o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vt.b, pf.b, o[dt], 0, 0, 0);
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+  l_run += __shfl_xor(l_run, 16, 64);
+  l_run += __shfl_xor(l_run, 32, 64);
+
+  // ---- merge the four waves (LDS reused after everyone is done with the V stages)
+  __syncthreads();
+  float* sm_o = reinterpret_cast<float*>(smem);            // [4][16][D]
+  float* sm_m = sm_o + 4 * 16 * D;                         // [4][16]
+  float* sm_l = sm_m + 64;                                 // [4][16]
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt)
+    *reinterpret_cast<f32x4*>(sm_o + ((size_t)wave * 16 + l16) * D + dt * 16 + gq * 4) = o[dt];
+  if (gq == 0) {
+    sm_m[wave * 16 + l16] = m_run;
+    sm_l[wave * 16 + l16] = l_run;
+  }
+  __syncthreads();
+  for (int idx = tid; idx < g * D; idx += 256) {
+    const int h = idx / D, col = idx % D;
+    float M = fmaxf(fmaxf(sm_m[h], sm_m[16 + h]), fmaxf(sm_m[32 + h], sm_m[48 + h]));
+    float acc = 0.f, L = 0.f;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+      const float mw = sm_m[w * 16 + h];
+      const float f = (mw == -INFINITY) ? 0.f : exp2f(mw - M);
+      acc += f * sm_o[((size_t)w * 16 + h) * D + col];
+      L += f * sm_l[w * 16 + h];
+    }
+    float* dst = part + (((size_t)b * nq + (size_t)kvh * g + h) * NCH + ch) * (D + 2);
+    dst[col] = acc;
+    if (col == 0) {
+      dst[D] = M;
+      dst[D + 1] = L;
+    }
+  }
+}
+
+template <int D>
+__global__ __launch_bounds__(D) void attn_decode_merge_kernel(const float* __restrict__ part,
+                                                              const int32_t* __restrict__ seq_lens,
+                                                              ts_bf16* __restrict__ out, int nq, int NCH) {
+  const int bh = blockIdx.x, b = bh / nq, col = threadIdx.x;
+  const int len = seq_lens[b];
+  ts_bf16* dst = out + (size_t)bh * D;
+  if (len <= 0) {
+    dst[col] = 0;
+    return;
+  }
+  const int nchunk = decode_nchunk(len, NCH);
+  const float* p = part + (size_t)bh * NCH * (D + 2);
+  float M = -INFINITY;
+  for (int c = 0; c < nchunk; ++c) M = fmaxf(M, p[(size_t)c * (D + 2) + D]);
+  float acc = 0.f, L = 0.f;
+  for (int c = 0; c < nchunk; ++c) {
+    const float mc = p[(size_t)c * (D + 2) + D];
+    const float f = (mc == -INFINITY) ? 0.f : exp2f(mc - M);
+    acc += f * p[(size_t)c * (D + 2) + col];
+    L += f * p[(size_t)c * (D + 2) + D + 1];
+  }
+  dst[col] = f_to_bf(acc / L);
+}
+
+namespace {
+int decode_nch(int B, int nkv, int Lcap) {
+  int want = cdiv(2048, B * nkv);
+  int cap = cdiv(Lcap, kMinChunk);
+  if (want > cap) want = cap;
+  if (want > 64) want = 64;
+  if (want < 1) want = 1;
+  return want;
+}
+}  // namespace
+
+size_t attention_decode_workspace_bytes(int B, int nq, int nkv, int d, int Lcap) {
+  if (B <= 0 || nq <= 0 || nkv <= 0 || d <= 0 || Lcap <= 0) return 0;
+  return (size_t)B * nq * decode_nch(B, nkv, Lcap) * (d + 2) * sizeof(float);
+}
+
+int launch_attention_decode(const ts_bf16* q, int q_stride, const ts_bf16* kc, const ts_bf16* vc, const int32_t* seq_lens,
+                            ts_bf16* out, int B, int nq, int nkv, int d, int Lcap, float scale, void* ws,
+                            size_t ws_bytes, hipStream_t s) {
+  if (B == 0) return TS_OK;
+  const int NCH = decode_nch(B, nkv, Lcap);
+  const size_t need = attention_decode_workspace_bytes(B, nq, nkv, d, Lcap);
+  TS_REQUIRE(ws != nullptr && ws_bytes >= need, TS_ERR_WORKSPACE,
+             "ts_attention_decode: workspace %zu bytes < required %zu", ws_bytes, need);
+  const float c_scale = scale * 1.4426950408889634f;
+  dim3 grid(NCH, nkv, B);
+  float* part = reinterpret_cast<float*>(ws);
+  if (d == 128) {
+    const size_t stage = (size_t)4 * kBlockKeys * 17 * sizeof(uint4);
+    const size_t merge = (size_t)(4 * 16 * 128 + 128) * sizeof(float);
+    const size_t smem = stage > merge ? stage : merge;
+    hipLaunchKernelGGL(attn_decode_split_kernel<128>, grid, dim3(256), smem, s, q, kc, vc, seq_lens, part, q_stride, nq,
+                       nkv, Lcap, NCH, c_scale);
+    TS_LAUNCH_CHECK("attn_decode_split");
+    hipLaunchKernelGGL(attn_decode_merge_kernel<128>, dim3(B * nq), dim3(128), 0, s, part, seq_lens, out, nq, NCH);
+  } else {
+    const size_t stage = (size_t)4 * kBlockKeys * 9 * sizeof(uint4);
+    const size_t merge = (size_t)(4 * 16 * 64 + 128) * sizeof(float);
+    const size_t smem = stage > merge ? stage : merge;
+    hipLaunchKernelGGL(attn_decode_split_kernel<64>, grid, dim3(256), smem, s, q, kc, vc, seq_lens, part, q_stride, nq,
+                       nkv, Lcap, NCH, c_scale);
+    TS_LAUNCH_CHECK("attn_decode_split");
+    hipLaunchKernelGGL(attn_decode_merge_kernel<64>, dim3(B * nq), dim3(64), 0, s, part, seq_lens, out, nq, NCH);
+  }
+  TS_LAUNCH_CHECK("attn_decode_merge");
+  return TS_OK;
+}
+
+}  // namespace ts

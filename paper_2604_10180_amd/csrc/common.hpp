@@ -1,0 +1,103 @@
+// Shared device/host helpers for the gfx950 decoder-layer kernels.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include "../../include/tessera.h"
+
+namespace ts {
+
+// ---- error plumbing (host) -------------------------------------------------
+void set_error(const char* fmt, ...);
+int fail(int code, const char* fmt, ...);
+int check_hip(hipError_t e, const char* what);
+
+#define TS_REQUIRE(cond, code, ...)            \
+  do {                                         \
+    if (!(cond)) return ::ts::fail((code), __VA_ARGS__); \
+  } while (0)
+
+#define TS_HIP(expr)                                         \
+  do {                                                       \
+    int _rc = ::ts::check_hip((expr), #expr);                \
+    if (_rc != TS_OK) return _rc;                            \
+  } while (0)
+
+// checks the launch that was just issued
+#define TS_LAUNCH_CHECK(name) TS_HIP(hipGetLastError())
+
+static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+static inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
+
+// ---- device vector types ----------------------------------------------------
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef float f32x2 __attribute__((ext_vector_type(2)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+
+union U4 {
+  uint4 u;
+  bf16x8 b;
+  uint32_t w[4];
+  uint16_t h[8];
+};
+
+__device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+__device__ __forceinline__ float bf_to_f(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+// two floats -> packed bf16 pair (round to nearest even; hardware v_cvt_pk_bf16_f32 on gfx950)
+__device__ __forceinline__ uint32_t pack_bf16(float lo, float hi) {
+  f32x2 v = {lo, hi};
+  bf16x2 b = __builtin_convertvector(v, bf16x2);
+  return __builtin_bit_cast(uint32_t, b);
+}
+__device__ __forceinline__ uint16_t f_to_bf(float f) {
+  __bf16 b = (__bf16)f;
+  return __builtin_bit_cast(uint16_t, b);
+}
+
+__device__ __forceinline__ uint4 ldg16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
+__device__ __forceinline__ void stg16(void* p, uint4 v) { *reinterpret_cast<uint4*>(p) = v; }
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}
+
+// ---- internal launchers (host), one per kernel family -----------------------
+int launch_rmsnorm(const ts_bf16* x, const ts_bf16* gamma, ts_bf16* y, int T, int H, float eps, hipStream_t s);
+int launch_swiglu(const ts_bf16* gu, ts_bf16* out, int T, int F, hipStream_t s);
+int launch_rope(ts_bf16* q, ts_bf16* k, const ts_bf16* v, int q_stride, int kv_stride, const int32_t* pos,
+                const int32_t* seq_id, const float* cos_sin, int table_len, ts_bf16* kcache, ts_bf16* vcache,
+                int T, int nq, int nkv, int d, int Lcap, float base, hipStream_t s);
+int launch_copy16(const void* src, void* dst, size_t bytes, hipStream_t s);
+
+size_t gemm_workspace_bytes(int M, int N, int K);
+int launch_gemm(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, void* C, bool f32out, int M, int N,
+                int K, void* ws, size_t ws_bytes, hipStream_t s);
+int launch_moe_gemm(const ts_bf16* A, const int32_t* row_map, int row_div, const ts_bf16* W,
+                    const int32_t* offsets, ts_bf16* C, int rows, int E, int N, int K, hipStream_t s);
+
+size_t attention_decode_workspace_bytes(int B, int nq, int nkv, int d, int Lcap);
+int launch_attention_decode(const ts_bf16* q, int q_stride, const ts_bf16* kc, const ts_bf16* vc, const int32_t* seq_lens,
+                            ts_bf16* out, int B, int nq, int nkv, int d, int Lcap, float scale, void* ws,
+                            size_t ws_bytes, hipStream_t s);
+int launch_attention_prefill(const ts_bf16* q, const ts_bf16* k, const ts_bf16* v, int q_stride, int kv_stride,
+                             const int32_t* cu, ts_bf16* out, int S, int T, int max_seqlen, int nq, int nkv, int d,
+                             float scale, int causal, hipStream_t s);
+
+int launch_moe_route(const float* logits, int T, int E, int k, int32_t* idx, float* w, int32_t* counts,
+                     int32_t* offsets, int32_t* perm, hipStream_t s);
+int launch_moe_combine(const ts_bf16* y, const int32_t* perm, const float* w, const ts_bf16* residual, ts_bf16* out,
+                       int32_t* inv, int T, int k, int H, hipStream_t s);
+
+}  // namespace ts

@@ -1,0 +1,468 @@
+// bf16 projections C = A * W^T on the gfx950 matrix cores.
+//
+// Two kernels, because the paper's regime split (Sec. 2.3) applies to the very same
+// product: with a handful of rows the weights are streamed once from HBM and the kernel is
+// bandwidth-bound ("skinny", also used per expert by the grouped MoE product); with
+// thousands of rows it is MFMA-bound ("tiled").
+//
+// Both use W as the MFMA "A" operand (rows = output columns n) and the activations as the
+// "B" operand (columns = token rows m), so each lane ends up with 4 consecutive n of one
+// token row and stores 8 contiguous bytes.  Both operands are K-contiguous in memory, so a
+// lane's 8-element operand fragment is one 16-byte load; which 8 k-values a lane group
+// holds is free as long as both operands agree, and is chosen for contiguous loads.
+#include "common.hpp"
+
+namespace ts {
+
+// ============================================================================ skinny
+struct SkinnyArgs {
+  const ts_bf16* A;
+  const int32_t* row_map;
+  int row_div;
+  const ts_bf16* W;
+  const int32_t* offsets;   // grouped only
+  const ts_bf16* residual;
+  void* C;                  // bf16 or f32 [M,N]
+  float* partial;           // [S,M,N] when S > 1
+  int M, N, K;
+  int kslice, S;
+  int f32out;
+  long w_group_stride;      // elements between experts
+};
+
+// Workgroup: 4 waves; wave w owns 16*NT rows of W; the activation k-slab [MT*16, 128] is
+// staged in LDS and shared by the 4 waves.  K advances 128 per iteration; lane (r, g) of a
+// wave (r = lane%16, g = lane/16) holds for MFMA step j the 8 k-values of 16-byte chunk
+// j*4+g, so a row's four lanes read 64 contiguous bytes per load.
+template <int MT, int NT, bool GROUPED>
+__global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs a) {
+  constexpr int ROWS = MT * 16;
+  constexpr int LDS_ROW = 17;  // uint4 per staged row: 16 data + 1 pad (272 B stride, conflict-free b128 reads)
+  extern __shared__ uint4 smem[];
+  uint4(*lds)[ROWS][LDS_ROW] = reinterpret_cast<uint4(*)[ROWS][LDS_ROW]>(smem);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int l16 = lane & 15, g = lane >> 4;
+  int row0 = 0, Mtot = a.M;
+  const ts_bf16* W = a.W;
+  if (GROUPED) {
+    const int e = blockIdx.z;
+    row0 = a.offsets[e];
+    Mtot = a.offsets[e + 1] - row0;
+    if (Mtot <= 0) return;
+    W += (size_t)e * a.w_group_stride;
+  }
+  const int N = a.N, K = a.K;
+  const int nbase = blockIdx.x * (64 * NT) + wave * (16 * NT);
+  const int kbeg = blockIdx.y * a.kslice;
+  const int kend = min(K, kbeg + a.kslice);
+
+  const ts_bf16* wrow[NT];
+#pragma unroll
+  for (int nt = 0; nt < NT; ++nt) {
+    int n = min(nbase + nt * 16 + l16, N - 1);
+    wrow[nt] = W + (size_t)n * K;
+  }
+  const int st_r = tid >> 4, st_c = tid & 15;  // staging: row st_r + 16*i, chunk st_c
+
+  for (int m0 = 0; m0 < Mtot; m0 += ROWS) {
+    const int Mcur = min(ROWS, Mtot - m0);
+    const ts_bf16* arow[MT];
+#pragma unroll
+    for (int i = 0; i < MT; ++i) {
+      int r = st_r + 16 * i;
+      long src = 0;
+      if (r < Mcur) {
+        src = (long)row0 + m0 + r;
+        if (a.row_map != nullptr) src = a.row_map[src] / a.row_div;
+      }
+      arow[i] = (r < Mcur) ? a.A + (size_t)src * K : nullptr;
+    }
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    U4 wreg[NT][4], wnext[NT][4], areg[MT];
+    const uint4 zero4 = make_uint4(0, 0, 0, 0);
+
+    auto load_w = [&](int k0, U4(&dst)[NT][4]) {
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          int k = k0 + (j * 4 + g) * 8;
+          dst[nt][j].u = (k < kend) ? ldg16(wrow[nt] + k) : zero4;
+        }
+    };
+    auto load_a = [&](int k0) {
+#pragma unroll
+      for (int i = 0; i < MT; ++i) {
+        int k = k0 + st_c * 8;
+        areg[i].u = (arow[i] != nullptr && k < kend) ? ldg16(arow[i] + k) : zero4;
+      }
+    };
+    auto store_a = [&](int buf) {
+#pragma unroll
+      for (int i = 0; i < MT; ++i) lds[buf][st_r + 16 * i][st_c] = areg[i].u;
+    };
+
+    load_w(kbeg, wreg);
+    load_a(kbeg);
+    store_a(0);
+    __syncthreads();
+    int it = 0;
+    for (int k0 = kbeg; k0 < kend; k0 += 128, ++it) {
+      const int cur = it & 1;
+      const bool more = (k0 + 128) < kend;
+      if (more) {
+        load_w(k0 + 128, wnext);
+        load_a(k0 + 128);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+          if (mt * 16 < Mcur) {
+            U4 b;
+            b.u = lds[cur][mt * 16 + l16][j * 4 + g];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+              acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[nt][j].b, b.b, acc[mt][nt], 0, 0, 0);
+          }
+        }
+      }
+      if (more) {
+        store_a(cur ^ 1);
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) wreg[nt][j] = wnext[nt][j];
+      }
+      __syncthreads();
+    }
+
+    // epilogue: lane holds D[n = g*4+i][m = l16] for every (mt, nt)
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+      const int ml = mt * 16 + l16;
+      if (ml >= Mcur) continue;
+      const size_t orow = (size_t)row0 + m0 + ml;
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        const int n = nbase + nt * 16 + g * 4;
+        if (n >= N) continue;
+        f32x4 v = acc[mt][nt];
+        if (a.S > 1) {
+          float* p = a.partial + ((size_t)blockIdx.y * a.M + orow) * N + n;
+          if ((N & 3) == 0) {
+            *reinterpret_cast<f32x4*>(p) = v;
+          } else {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              if (n + i < N) p[i] = v[i];
+          }
+          continue;
+        }
+        const size_t o = orow * N + n;
+        if (a.f32out) {
+          float* p = reinterpret_cast<float*>(a.C) + o;
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (n + i < N) p[i] = v[i];
+          continue;
+        }
+        ts_bf16* cp = reinterpret_cast<ts_bf16*>(a.C) + o;
+        if ((N & 3) == 0) {
+          if (a.residual != nullptr) {
+            uint2 r = *reinterpret_cast<const uint2*>(a.residual + o);
+            v[0] += bf_lo(r.x); v[1] += bf_hi(r.x); v[2] += bf_lo(r.y); v[3] += bf_hi(r.y);
+          }
+          uint2 out;
+          out.x = pack_bf16(v[0], v[1]);
+          out.y = pack_bf16(v[2], v[3]);
+          *reinterpret_cast<uint2*>(cp) = out;
+        } else {
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+            if (n + i < N) {
+              float x = v[i];
+              if (a.residual != nullptr) x += bf_to_f(a.residual[o + i]);
+              cp[i] = f_to_bf(x);
+            }
+        }
+      }
+    }
+  }
+}
+
+// out[m,n] = sum_s partial[s,m,n] (+ residual), slices added in ascending s (deterministic).
+__global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial,
+                                                            const ts_bf16* __restrict__ residual, void* C, long MN,
+                                                            int S, int f32out) {
+  long i = ((long)blockIdx.x * 256 + threadIdx.x) * 2;
+  if (i >= MN) return;
+  float a0 = 0.f, a1 = 0.f;
+  for (int s = 0; s < S; ++s) {
+    float2 p = *reinterpret_cast<const float2*>(partial + (size_t)s * MN + i);
+    a0 += p.x;
+    a1 += p.y;
+  }
+  if (f32out) {
+    *reinterpret_cast<float2*>(reinterpret_cast<float*>(C) + i) = make_float2(a0, a1);
+    return;
+  }
+  if (residual != nullptr) {
+    uint32_t r = *reinterpret_cast<const uint32_t*>(residual + i);
+    a0 += bf_lo(r);
+    a1 += bf_hi(r);
+  }
+  *reinterpret_cast<uint32_t*>(reinterpret_cast<ts_bf16*>(C) + i) = pack_bf16(a0, a1);
+}
+
+// ============================================================================ tiled
+// Block tile BM (token rows) x BN (W rows), BK = 64, 4 waves as 2 (n) x 2 (m); every wave
+// computes (BN/2) x (BM/2) with 32x32x16 MFMAs.  Both operand tiles go global -> registers
+// -> LDS (144-byte row stride: conflict-free 16-byte operand reads), double buffered, one
+// barrier per K step.
+template <int BM, int BN, bool F32OUT>
+__global__ __launch_bounds__(256) void gemm_tiled_kernel(const ts_bf16* __restrict__ A, const ts_bf16* __restrict__ W,
+                                                         const ts_bf16* __restrict__ residual, void* __restrict__ C,
+                                                         int M, int N, int K, int tiles_m) {
+  constexpr int TN = BN / 64, TM = BM / 64;
+  constexpr int LW = BN / 32, LA = BM / 32;  // 16-byte chunks per thread per tile
+  extern __shared__ uint4 smem[];
+  // layout: [2][BN][9] then [2][BM][9]
+  uint4(*sW)[BN][9] = reinterpret_cast<uint4(*)[BN][9]>(smem);
+  uint4(*sA)[BM][9] = reinterpret_cast<uint4(*)[BM][9]>(smem + 2 * BN * 9);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int r32 = lane & 31, g = lane >> 5;
+  const int wn = wave & 1, wm = wave >> 1;
+  const int tile_m = blockIdx.x % tiles_m, tile_n = blockIdx.x / tiles_m;
+  const int mb = tile_m * BM, nb = tile_n * BN;
+
+  const int st_r = tid >> 3, st_c = tid & 7;
+  const ts_bf16* wptr[LW];
+  const ts_bf16* aptr[LA];
+#pragma unroll
+  for (int i = 0; i < LW; ++i) wptr[i] = W + (size_t)min(nb + st_r + 32 * i, N - 1) * K + st_c * 8;
+#pragma unroll
+  for (int i = 0; i < LA; ++i) aptr[i] = A + (size_t)min(mb + st_r + 32 * i, M - 1) * K + st_c * 8;
+
+  f32x16 acc[TN][TM];
+#pragma unroll
+  for (int i = 0; i < TN; ++i)
+#pragma unroll
+    for (int j = 0; j < TM; ++j)
+#pragma unroll
+      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+
+  uint4 wr[LW], ar[LA];
+  const uint4 zero4 = make_uint4(0, 0, 0, 0);
+  auto gload = [&](int k0) {
+    const bool ok = (k0 + st_c * 8) < K;
+#pragma unroll
+    for (int i = 0; i < LW; ++i) wr[i] = ok ? ldg16(wptr[i] + k0) : zero4;
+#pragma unroll
+    for (int i = 0; i < LA; ++i) ar[i] = ok ? ldg16(aptr[i] + k0) : zero4;
+  };
+  auto sstore = [&](int buf) {
+#pragma unroll
+    for (int i = 0; i < LW; ++i) sW[buf][st_r + 32 * i][st_c] = wr[i];
+#pragma unroll
+    for (int i = 0; i < LA; ++i) sA[buf][st_r + 32 * i][st_c] = ar[i];
+  };
+
+  gload(0);
+  sstore(0);
+  __syncthreads();
+  int it = 0;
+  for (int k0 = 0; k0 < K; k0 += 64, ++it) {
+    const int cur = it & 1;
+    const bool more = (k0 + 64) < K;
+    if (more) gload(k0 + 64);
+#pragma unroll
+    for (int ks = 0; ks < 4; ++ks) {
+      U4 wf[TN], af[TM];
+#pragma unroll
+      for (int i = 0; i < TN; ++i) wf[i].u = sW[cur][wn * (BN / 2) + i * 32 + r32][ks * 2 + g];
+#pragma unroll
+      for (int j = 0; j < TM; ++j) af[j].u = sA[cur][wm * (BM / 2) + j * 32 + r32][ks * 2 + g];
+#pragma unroll
+      for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+          acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i].b, af[j].b, acc[i][j], 0, 0, 0);
+    }
+    if (more) sstore(cur ^ 1);
+    __syncthreads();
+  }
+
+  // epilogue: acc[i][j][e] is D[n = (e/4)*8 + g*4 + e%4][m = r32] of the 32x32 tile
+#pragma unroll
+  for (int j = 0; j < TM; ++j) {
+    const int m = mb + wm * (BM / 2) + j * 32 + r32;
+    if (m >= M) continue;
+#pragma unroll
+    for (int i = 0; i < TN; ++i) {
+#pragma unroll
+      for (int gi = 0; gi < 4; ++gi) {
+        const int n = nb + wn * (BN / 2) + i * 32 + gi * 8 + g * 4;
+        if (n >= N) continue;
+        float v[4] = {acc[i][j][gi * 4 + 0], acc[i][j][gi * 4 + 1], acc[i][j][gi * 4 + 2], acc[i][j][gi * 4 + 3]};
+        const size_t o = (size_t)m * N + n;
+        if (F32OUT) {
+          float* p = reinterpret_cast<float*>(C) + o;
+#pragma unroll
+          for (int e = 0; e < 4; ++e)
+            if (n + e < N) p[e] = v[e];
+        } else {
+          ts_bf16* cp = reinterpret_cast<ts_bf16*>(C) + o;
+          if ((N & 3) == 0) {
+            if (residual != nullptr) {
+              uint2 r = *reinterpret_cast<const uint2*>(residual + o);
+              v[0] += bf_lo(r.x); v[1] += bf_hi(r.x); v[2] += bf_lo(r.y); v[3] += bf_hi(r.y);
+            }
+            uint2 out;
+            out.x = pack_bf16(v[0], v[1]);
+            out.y = pack_bf16(v[2], v[3]);
+            *reinterpret_cast<uint2*>(cp) = out;
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (n + e < N) {
+                float x = v[e];
+                if (residual != nullptr) x += bf_to_f(residual[o + e]);
+                cp[e] = f_to_bf(x);
+              }
+          }
+        }
+      }
+    }
+  }
+}
+
+// ============================================================================ host side
+namespace {
+
+constexpr int kSkinnyMaxM = 128;
+
+struct SkinnyPlan {
+  int NT, S, kslice;
+};
+
+SkinnyPlan plan_skinny(int N, int K) {
+  SkinnyPlan p;
+  const int t2 = cdiv(N, 128), t1 = cdiv(N, 64);
+  p.S = 1;
+  if (t2 >= 448) {
+    p.NT = 2;
+  } else {
+    p.NT = 1;
+    if (t1 < 448) {
+      int want = cdiv(512, t1);
+      int maxs = K / 512;  // keep at least four 128-wide K steps per slice
+      if (maxs < 1) maxs = 1;
+      p.S = want < maxs ? want : maxs;
+      if (p.S > 16) p.S = 16;
+    }
+  }
+  p.kslice = (int)round_up((size_t)cdiv(K, p.S), 128);
+  p.S = cdiv(K, p.kslice);
+  return p;
+}
+
+// Kernels that need more than the default dynamic-LDS limit raise it once.
+template <typename KernelT>
+void allow_lds(KernelT kernel, size_t bytes) {
+  if (bytes > 48 * 1024)
+    (void)hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                              (int)bytes);
+}
+
+template <int MT, bool GROUPED>
+void launch_skinny_mt(const SkinnyArgs& a, int NT, dim3 grid, hipStream_t s) {
+  const size_t smem = (size_t)2 * MT * 16 * 17 * sizeof(uint4);
+  if (NT == 2) {
+    allow_lds(gemm_skinny_kernel<MT, 2, GROUPED>, smem);
+    hipLaunchKernelGGL((gemm_skinny_kernel<MT, 2, GROUPED>), grid, dim3(256), smem, s, a);
+  } else {
+    allow_lds(gemm_skinny_kernel<MT, 1, GROUPED>, smem);
+    hipLaunchKernelGGL((gemm_skinny_kernel<MT, 1, GROUPED>), grid, dim3(256), smem, s, a);
+  }
+}
+
+template <bool GROUPED>
+void launch_skinny(const SkinnyArgs& a, int mrows, int NT, dim3 grid, hipStream_t s) {
+  if (mrows <= 16) launch_skinny_mt<1, GROUPED>(a, NT, grid, s);
+  else if (mrows <= 32) launch_skinny_mt<2, GROUPED>(a, NT, grid, s);
+  else if (mrows <= 64) launch_skinny_mt<4, GROUPED>(a, NT, grid, s);
+  else launch_skinny_mt<8, GROUPED>(a, NT, grid, s);
+}
+
+}  // namespace
+
+size_t gemm_workspace_bytes(int M, int N, int K) {
+  if (M <= 0 || N <= 0 || K <= 0 || M > kSkinnyMaxM) return 0;
+  SkinnyPlan p = plan_skinny(N, K);
+  return p.S > 1 ? (size_t)p.S * M * N * sizeof(float) : 0;
+}
+
+int launch_gemm(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, void* C, bool f32out, int M, int N, int K,
+                void* ws, size_t ws_bytes, hipStream_t s) {
+  if (M == 0) return TS_OK;
+  if (M <= kSkinnyMaxM) {
+    SkinnyPlan p = plan_skinny(N, K);
+    const size_t need = p.S > 1 ? (size_t)p.S * M * N * sizeof(float) : 0;
+    TS_REQUIRE(need == 0 || (ws != nullptr && ws_bytes >= need), TS_ERR_WORKSPACE,
+               "ts_gemm_bf16: workspace %zu bytes < required %zu", ws_bytes, need);
+    SkinnyArgs a{};
+    a.A = A; a.row_map = nullptr; a.row_div = 1; a.W = W; a.offsets = nullptr; a.residual = residual; a.C = C;
+    a.partial = reinterpret_cast<float*>(ws); a.M = M; a.N = N; a.K = K; a.kslice = p.kslice; a.S = p.S;
+    a.f32out = f32out ? 1 : 0; a.w_group_stride = 0;
+    dim3 grid(cdiv(N, 64 * p.NT), p.S, 1);
+    launch_skinny<false>(a, M, p.NT, grid, s);
+    TS_LAUNCH_CHECK("gemm_skinny");
+    if (p.S > 1) {
+      long MN = (long)M * N;
+      hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((MN / 2 + 255) / 256)), dim3(256), 0, s,
+                         reinterpret_cast<const float*>(ws), residual, C, MN, p.S, f32out ? 1 : 0);
+      TS_LAUNCH_CHECK("splitk_reduce");
+    }
+    return TS_OK;
+  }
+  constexpr int BM = 128, BN = 128;
+  const int tiles_m = cdiv(M, BM), tiles_n = cdiv(N, BN);
+  const size_t smem = (size_t)2 * (BM + BN) * 9 * sizeof(uint4);
+  dim3 grid(tiles_m * tiles_n);
+  if (f32out) {
+    allow_lds(gemm_tiled_kernel<BM, BN, true>, smem);
+    hipLaunchKernelGGL((gemm_tiled_kernel<BM, BN, true>), grid, dim3(256), smem, s, A, W, residual, C, M, N, K, tiles_m);
+  } else {
+    allow_lds(gemm_tiled_kernel<BM, BN, false>, smem);
+    hipLaunchKernelGGL((gemm_tiled_kernel<BM, BN, false>), grid, dim3(256), smem, s, A, W, residual, C, M, N, K, tiles_m);
+  }
+  TS_LAUNCH_CHECK("gemm_tiled");
+  return TS_OK;
+}
+
+int launch_moe_gemm(const ts_bf16* A, const int32_t* row_map, int row_div, const ts_bf16* W, const int32_t* offsets,
+                    ts_bf16* C, int rows, int E, int N, int K, hipStream_t s) {
+  if (rows == 0) return TS_OK;
+  SkinnyArgs a{};
+  a.A = A; a.row_map = row_map; a.row_div = row_div; a.W = W; a.offsets = offsets; a.residual = nullptr; a.C = C;
+  a.partial = nullptr; a.M = rows; a.N = N; a.K = K; a.kslice = (int)round_up((size_t)K, 128); a.S = 1; a.f32out = 0;
+  a.w_group_stride = (long)N * K;
+  const int NT = (cdiv(N, 128) * E >= 448) ? 2 : 1;
+  dim3 grid(cdiv(N, 64 * NT), 1, E);
+  // Row tile: sized for the average expert load; larger experts loop over row blocks.
+  const int avg = cdiv(rows, E);
+  const int mrows = avg <= 8 ? 16 : (avg <= 20 ? 32 : (avg <= 44 ? 64 : 128));
+  launch_skinny<true>(a, mrows, NT, grid, s);
+  TS_LAUNCH_CHECK("moe_gemm");
+  return TS_OK;
+}
+
+}  // namespace ts

@@ -1,0 +1,234 @@
+"""Whole-layer and pipelined-step parity at small sizes (every boundary tensor is compared),
+including the MoE layer with teacher-forced routing and the prefill -> decode hand-over."""
+import numpy as np
+import pytest
+import torch
+
+import workloads as WL
+from oracle import decoder_layer as O
+from parity import assert_close, to_np
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module")
+def B():
+    assert torch.cuda.is_available()
+    from paper_2604_10180_amd import binding
+    return binding
+
+
+def run_layer(B, wl, weights, io, use_table=False):
+    """Runs ts_layer_forward; returns dict of boundary tensors (numpy f64) + caches."""
+    s = wl.shape
+    Lcap = io["kcache"].shape[2]
+    T = io["x"].shape[0]
+    Bs = io["kcache"].shape[0]
+    wd = {k: v.to(DEV) for k, v in weights.items()}
+    iod = {k: v.to(DEV) for k, v in io.items()}
+    out = torch.empty(T, s.H, dtype=torch.bfloat16, device=DEV)
+    desc = B.make_desc(s, Lcap, wl.mode)
+    table = None
+    if use_table:
+        th = torch.empty(Lcap, s.d, dtype=torch.float32)
+        B.ts_rope_table(th, Lcap, s.d, s.rope_base)
+        table = th.to(DEV)
+    nbytes = B.ts_layer_workspace_bytes(desc, T, Bs)
+    ws = torch.zeros(nbytes, dtype=torch.uint8, device=DEV)
+    max_seqlen = int(io["seq_lens"].max()) if wl.mode == "prefill" else 0
+    B.ts_layer_forward(desc, B.make_weights(wd, table), B.make_io(iod, out, T, Bs, max_seqlen), ws)
+    torch.cuda.synchronize()
+    names = O.BOUNDARY_ORDER_MOE if s.E else O.BOUNDARY_ORDER_DENSE
+    names = [n for n in names if n != "logits"]
+    res = {}
+    for i, n in enumerate(names):
+        off, nb = B.ts_layer_boundary(desc, T, Bs, i)
+        if off is None:
+            res[n] = to_np(out)
+        else:
+            res[n] = to_np(ws[off:off + nb].view(torch.bfloat16))
+    if s.E:
+        offs = B.ts_layer_moe_buffers(desc, T, Bs)
+        k = s.k
+        res["logits"] = ws[offs[0]:offs[0] + T * s.E * 4].view(torch.float32).cpu().numpy().reshape(T, s.E)
+        res["topk_idx"] = ws[offs[1]:offs[1] + T * k * 4].view(torch.int32).cpu().numpy().reshape(T, k)
+        res["topk_w"] = ws[offs[2]:offs[2] + T * k * 4].view(torch.float32).cpu().numpy().reshape(T, k)
+        res["counts"] = ws[offs[3]:offs[3] + s.E * 4].view(torch.int32).cpu().numpy()
+        res["offsets"] = ws[offs[4]:offs[4] + (s.E + 1) * 4].view(torch.int32).cpu().numpy()
+        res["perm"] = ws[offs[5]:offs[5] + T * k * 4].view(torch.int32).cpu().numpy()
+    res["kcache"] = to_np(iod["kcache"])
+    res["vcache"] = to_np(iod["vcache"])
+    return res
+
+
+def oracle_layer(wl, weights, io, **kw):
+    w64 = {k: WL.as_f64(v) for k, v in weights.items()}
+    io64 = {k: WL.as_f64(v) for k, v in io.items()}
+    r = O.layer_forward(wl.shape, w64, io64, wl.mode, **kw)
+    r["kcache"], r["vcache"] = io64["kcache"], io64["vcache"]
+    return r
+
+
+def compare_layer(got, ref, names):
+    for n in names:
+        assert_close(got[n].reshape(-1), ref[n].reshape(-1), f"boundary {n}")
+    assert_close(got["kcache"], ref["kcache"], "kcache")
+    assert_close(got["vcache"], ref["vcache"], "vcache")
+
+
+@pytest.mark.parametrize("use_table", [False, True])
+def test_tiny_decode_layer_all_boundaries(B, use_table):
+    wl = WL.CONFIGS["tiny"]
+    weights, io, _ = WL.build(wl)
+    got = run_layer(B, wl, weights, io, use_table)
+    ref = oracle_layer(wl, weights, io)
+    compare_layer(got, ref, O.BOUNDARY_ORDER_DENSE)
+
+
+def test_small_ragged_decode_layer_nan_tail(B):
+    """Ragged lengths, unused cache tail poisoned with NaN: nothing beyond seq_lens may be read."""
+    wl = WL.scaled(WL.CONFIGS["tiny"], B=5)
+    weights, io, _ = WL.build(wl, seed=3, ctx_lens=[0, 1, 31, 300, 77], tail_fill=float("nan"))
+    got = run_layer(B, wl, weights, io)
+    io_o = {k: (torch.nan_to_num(v, nan=0.0) if v.is_floating_point() else v) for k, v in io.items()}
+    ref = oracle_layer(wl, weights, io_o)
+    for n in O.BOUNDARY_ORDER_DENSE:
+        assert_close(got[n].reshape(-1), ref[n].reshape(-1), f"boundary {n}")
+
+
+def test_mid_decode_layer_gqa8(B):
+    """A 70B-like head layout (GQA group 8, d=128) at reduced width."""
+    shape = WL.LayerShape(H=1024, nq=16, nkv=2, d=128, F=2816)
+    wl = WL.Workload("mid", shape, "decode", B=6)
+    weights, io, _ = WL.build(wl, seed=1, ctx_lens=[512, 1500, 33, 2048, 700, 1])
+    got = run_layer(B, wl, weights, io, use_table=True)
+    ref = oracle_layer(wl, weights, io)
+    compare_layer(got, ref, O.BOUNDARY_ORDER_DENSE)
+
+
+def test_small_prefill_layer_then_decode(B):
+    shape = WL.LayerShape(H=512, nq=8, nkv=2, d=64, F=1376)
+    wl = WL.Workload("pre", shape, "prefill", B=3, seq_tokens=0)
+    gen = torch.Generator().manual_seed(7)
+    weights = WL.make_weights(shape, gen)
+    seqs = [70, 1, 130]
+    io = WL.make_prefill_io(shape, seqs, gen, Lcap=140)
+    got = run_layer(B, wl, weights, io)
+    ref = oracle_layer(wl, weights, io)
+    compare_layer(got, ref, O.BOUNDARY_ORDER_DENSE)
+    # decode one more token per sequence over the cache the GPU prefill wrote
+    wl_d = WL.Workload("dec", shape, "decode", B=3)
+    io_d = {"x": WL.randn_bf16(gen, 3, shape.H), "pos": torch.tensor(seqs, dtype=torch.int32),
+            "seq_id": torch.arange(3, dtype=torch.int32), "seq_lens": torch.tensor(seqs, dtype=torch.int32) + 1,
+            "kcache": torch.tensor(got["kcache"]).to(torch.bfloat16), "vcache": torch.tensor(got["vcache"]).to(torch.bfloat16)}
+    got_d = run_layer(B, wl_d, weights, io_d)
+    ref_d = oracle_layer(wl_d, weights, io_d)
+    compare_layer(got_d, ref_d, O.BOUNDARY_ORDER_DENSE)
+
+
+def test_small_moe_layer_teacher_forced(B):
+    shape = WL.LayerShape(H=512, nq=8, nkv=2, d=64, F=688, E=8, k=2)
+    wl = WL.Workload("moe", shape, "decode", B=48)
+    weights, io, _ = WL.build(wl, seed=2, ctx_lens=[100 + 3 * i for i in range(48)])
+    got = run_layer(B, wl, weights, io)
+    ref_free = oracle_layer(wl, weights, io)
+    for n in ("h1", "qkv", "attn", "x2", "h2"):
+        assert_close(got[n].reshape(-1), ref_free[n].reshape(-1), f"boundary {n}")
+    assert_close(got["logits"], ref_free["logits"], "router logits", max_abs=2e-2, rel_l2=5e-3)
+    # routing is exact given the logits the GPU produced (same fp32 values on both sides)
+    idx, w, counts, offsets, perm = O.moe_route(got["logits"], shape.k)
+    assert np.array_equal(got["topk_idx"], idx)
+    assert np.array_equal(got["counts"], counts)
+    assert np.array_equal(got["offsets"], offsets)
+    assert np.array_equal(got["perm"], perm)
+    assert np.allclose(got["topk_w"], w, atol=2e-7)
+    # teacher-forced: the oracle layer takes the GPU's routing decision, everything else its own
+    ref = oracle_layer(wl, weights, io, forced_route=(idx, w))
+    for n in ("gate_up", "act", "y", "out"):
+        assert_close(got[n].reshape(-1), ref[n].reshape(-1), f"boundary {n}")
+    # and un-forced routing agrees wherever the top-k margin is clear of bf16 noise
+    srt = np.sort(ref_free["logits"], axis=1)[:, ::-1]
+    clear = (srt[:, shape.k - 1] - srt[:, shape.k]) > 2e-2
+    assert np.array_equal(got["topk_idx"][clear], ref_free["topk_idx"][clear])
+
+
+def _pipeline_case(B, wl, weights, io, n_mb, mask):
+    s = wl.shape
+    Lcap = io["kcache"].shape[2]
+    per = wl.B // n_mb
+    wd = {k: v.to(DEV) for k, v in weights.items()}
+    desc = B.make_desc(s, Lcap, "decode")
+    wts = B.make_weights(wd)
+    # reference runs: one ts_layer_forward per micro-batch on private cache copies
+    singles, ios_dev, outs = [], [], []
+    for i in range(n_mb):
+        sl = slice(i * per, (i + 1) * per)
+        iod = {k: (v[sl].clone().to(DEV) if k != "seq_id" else torch.arange(per, dtype=torch.int32, device=DEV))
+               for k, v in io.items()}
+        out = torch.empty(per, s.H, dtype=torch.bfloat16, device=DEV)
+        ws1 = torch.zeros(B.ts_layer_workspace_bytes(desc, per, per), dtype=torch.uint8, device=DEV)
+        iod1 = {k: v.clone() for k, v in iod.items()}
+        B.ts_layer_forward(desc, wts, B.make_io(iod1, out, per, per), ws1)
+        torch.cuda.synchronize()
+        rows = []
+        nb = B.TS_NB_DENSE
+        for j in range(nb):
+            if not (mask >> j) & 1:
+                continue
+            off, nbytes = B.ts_layer_boundary(desc, per, per, j)
+            rows.append(out.view(torch.uint8).reshape(-1).clone() if off is None else ws1[off:off + nbytes].clone())
+        singles.append((out.clone(), torch.cat(rows) if rows else torch.zeros(0, dtype=torch.uint8, device=DEV),
+                        iod1["kcache"].clone()))
+        ios_dev.append(iod)
+        outs.append(torch.empty(per, s.H, dtype=torch.bfloat16, device=DEV))
+    stride = B.ts_pipeline_slot_stride(desc, per, per, mask)
+    layout = B.ts_pipeline_boundary_layout(desc, per, per, mask)
+    staging = torch.zeros(max(stride * n_mb, 16), dtype=torch.uint8, device=DEV)
+    host = torch.zeros(max(stride * n_mb, 16), dtype=torch.uint8).pin_memory()
+    half = (B.ts_layer_workspace_bytes(desc, per, per) + 255) // 256 * 256
+    ws = torch.zeros(2 * half, dtype=torch.uint8, device=DEV)
+    pipe = B.ts_pipeline_create(desc, n_mb)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    copy = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    try:
+        for rep in range(2):       # second repetition reuses staging slots and workspace halves
+            mbs = [B.make_io({k: v.clone() if k in ("kcache", "vcache") else v for k, v in ios_dev[i].items()},
+                             outs[i], per, per) for i in range(n_mb)]
+            keep = mbs  # noqa: F841  (cloned caches are referenced only through raw pointers)
+            caches = [{k: v.clone() for k, v in ios_dev[i].items()} for i in range(n_mb)]
+            mbs = [B.make_io(caches[i], outs[i], per, per) for i in range(n_mb)]
+            host.zero_()
+            B.ts_pipeline_step(pipe, wts, mbs, streams, copy, mask, staging, host, ws)
+            for st in streams + [copy]:
+                st.synchronize()
+            for i in range(n_mb):
+                assert torch.equal(outs[i], singles[i][0]), f"micro-batch {i}: output differs from the single-stream layer"
+                assert torch.equal(caches[i]["kcache"], singles[i][2])
+                got = host[i * stride:i * stride + layout[-1]]
+                assert torch.equal(got, singles[i][1].cpu()), f"micro-batch {i}: pinned-host boundary bytes differ"
+    finally:
+        B.ts_pipeline_destroy(pipe)
+    return singles, layout
+
+
+@pytest.mark.parametrize("mask", [~0, 0b10001000, 0])
+def test_pipeline_step_matches_single_stream_and_oracle(B, mask):
+    wl = WL.scaled(WL.CONFIGS["tiny"], B=8)
+    weights, io, lens = WL.build(wl, seed=5, ctx_lens=[128, 64, 1, 300, 17, 200, 5, 90])
+    mask &= 0xFF
+    singles, layout = _pipeline_case(B, wl, weights, io, 4, mask)
+    # and the shipped bytes are the oracle's boundary tensors within tolerance
+    per = 2
+    for i in range(4):
+        sl = slice(i * per, (i + 1) * per)
+        io_i = {k: v[sl] for k, v in io.items()}
+        io_i["seq_id"] = torch.arange(per, dtype=torch.int32)
+        w64 = {k: WL.as_f64(v) for k, v in weights.items()}
+        r = O.layer_forward(wl.shape, w64, {k: WL.as_f64(v) for k, v in io_i.items()}, "decode")
+        ref = O.boundary_stream(r, moe=False, mask=mask)
+        got = singles[i][1].view(torch.bfloat16)
+        assert got.numel() == ref.size
+        if ref.size:
+            assert_close(got, ref, f"micro-batch {i} boundary stream")

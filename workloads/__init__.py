@@ -22,7 +22,7 @@ w_gate_up, w_down) -> x -> per sequence: K rows then V rows.
 The five named workloads mirror the five benchmark configurations (tiny layer,
 8B-shaped decode, 8B-shaped prefill, 8-expert top-2 MoE decode, 70B-shaped
 ragged decode run as four micro-batches).  They stand in for the model shapes
-and context lengths of the paper's serving experiments (Sec. 6.1), whose
+and context lengths of the paper's serving experiments (Sec. 5.1), whose
 weights and request traces are not available; only shapes and rough context
 lengths carry over.
 """
@@ -209,3 +209,8 @@ def micro_batches(wl: Workload) -> List[range]:
 def scaled(wl: Workload, **kw) -> Workload:
     """A smaller/larger variant of a named workload (tests use it for quick cases)."""
     return replace(wl, **kw)
+
+
+def randn_bf16(gen: torch.Generator, *shape, std: float = 1.0, mean: float = 0.0) -> torch.Tensor:
+    """A seeded N(mean, std) tensor rounded once to bf16 (for per-kernel test inputs)."""
+    return _randn(gen, *shape, std=std, mean=mean)
