@@ -1,0 +1,234 @@
+#!/usr/bin/env python3
+"""Decode-layer throughput on one MI355X + per-kernel roofline + CPU-oracle baseline.
+
+One "step" is one pass of the whole hot path (ts_layer_forward: RMSNorm, QKV, RoPE + KV
+append, attention, O, RMSNorm, MLP or MoE) over one synthetic batch already resident in HBM.
+The default workload is the Llama-8B-shaped bf16 decode layer (batch 64, context 2048).
+
+Prints ONE JSON line.  `value` = tokens/s of the timed region (plain calls, no profiling).
+`roofline` describes the dominant kernel, timed live with HIP events around every launch in a
+second pass over the same inputs; `kernels` lists all launches of one step the same way.
+`cpu_baseline` times the fp64 numpy oracle on the host on the same inputs (a reported
+baseline, not a target).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
+
+
+def kernel_models(wl, lens):
+    """Algorithmic HBM bytes and flops of every launch of one step, in launch order.
+
+    Bytes are what the method must move once: weights once, activations in and out once,
+    K and V rows of the attended positions once.  Returns list of (family, label, bytes, flops, bound).
+    """
+    s = wl.shape
+    T = wl.T
+    nqd, nkd = s.nq * s.d, s.nkv * s.d
+    nqkv = nqd + 2 * nkd
+
+    def gemm(label, M, N, K, res=False, split=True, grouped_E=0):
+        b = 2 * N * K * max(1, grouped_E) + 2 * M * K + 2 * M * N + (2 * M * N if res else 0)
+        f = 2 * M * N * K
+        return ("gemm", label, b, f)
+
+    out = []
+    out.append(("rmsnorm", "rmsnorm1", T * s.H * 4 + s.H * 2, 0))
+    out.append(gemm("qkv", T, nqkv, s.H))
+    out.append(("rope", "rope+append", T * (s.nq + s.nkv) * s.d * 4 + T * nkd * 2 + 2 * T * nkd * 2, 0))
+    if wl.mode == "decode":
+        keys = sum(int(L) + 1 for L in lens)
+        out.append(("attn_decode", "attention", keys * 2 * nkd * 2 + 2 * T * nqd * 2, 4 * s.nq * s.d * keys))
+    else:
+        fl = sum(4 * s.nq * s.d * n * (n + 1) // 2 for n in lens)
+        out.append(("attn_prefill", "attention", T * nqkv * 2 + T * nqd * 2, fl))
+    out.append(gemm("o", T, s.H, nqd, res=True))
+    out.append(("rmsnorm", "rmsnorm2", T * s.H * 4 + s.H * 2, 0))
+    if s.E == 0:
+        out.append(gemm("gate_up", T, 2 * s.F, s.H))
+        out.append(("swiglu", "swiglu", T * s.F * 6, 0))
+        out.append(gemm("down", T, s.H, s.F, res=True))
+    else:
+        R = T * s.k
+        out.append(gemm("router", T, s.E, s.H))
+        out.append(("moe_route", "route", T * s.E * 4 + R * 12 + s.E * 8, 0))
+        out.append(("gemm", "expert gate_up", 2 * 2 * s.F * s.H * s.E + 2 * R * s.H + 2 * R * 2 * s.F, 2 * R * 2 * s.F * s.H))
+        out.append(("swiglu", "swiglu", R * s.F * 6, 0))
+        out.append(("gemm", "expert down", 2 * s.H * s.F * s.E + 2 * R * s.F + 2 * R * s.H, 2 * R * s.H * s.F))
+        out.append(("moe_combine", "combine", R * s.H * 2 + T * s.H * 4, 0))
+    return out
+
+
+FAMILY_OF_LAUNCH = {
+    "rmsnorm": "rmsnorm", "gemm_skinny": "gemm", "gemm_tiled": "gemm", "splitk_reduce": None, "rope": "rope",
+    "attn_decode_split": "attn_decode", "attn_decode_merge": None, "attn_prefill": "attn_prefill",
+    "swiglu": "swiglu", "moe_topk": "moe_route", "moe_group": None, "moe_invert": None, "moe_combine": "moe_combine",
+    "copy16": None,
+}
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--workload", default="8b_decode")
+    ap.add_argument("--copies", type=int, default=2, help="rotated copies of weights+KV (defeats cache reuse across steps)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build is the one-GPU hot path of the method; there is no multi-GPU path to time "
+              "(run with --gpus 1).", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads as WL
+    from paper_2604_10180_amd import binding as B
+
+    wl = WL.CONFIGS[args.workload]
+    s = wl.shape
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    t0 = time.time()
+    weights, io, lens = WL.build(wl)
+    Lcap = io["kcache"].shape[2]
+    T, Bs = wl.T, wl.B
+    desc = B.make_desc(s, Lcap, wl.mode)
+    table_h = torch.empty(Lcap, s.d, dtype=torch.float32)
+    B.ts_rope_table(table_h, Lcap, s.d, s.rope_base)
+    sets = []
+    for c in range(max(1, args.copies)):
+        wd = {k: v.to(dev) for k, v in weights.items()}
+        iod = {k: v.to(dev) for k, v in io.items()}
+        out = torch.empty(T, s.H, dtype=torch.bfloat16, device=dev)
+        table = table_h.to(dev)
+        sets.append((wd, iod, out, B.make_weights(wd, table), table))
+    ws = torch.empty(B.ts_layer_workspace_bytes(desc, T, Bs), dtype=torch.uint8, device=dev)
+    max_seqlen = int(max(lens)) if wl.mode == "prefill" else 0
+    ios = [B.make_io(st[1], st[2], T, Bs, max_seqlen) for st in sets]
+    setup_s = time.time() - t0
+
+    def step(i):
+        st = sets[i % len(sets)]
+        B.ts_layer_forward(desc, st[3], ios[i % len(sets)], ws)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    e0.record()
+    for i in range(args.steps):
+        step(i)
+    e1.record()
+    torch.cuda.synchronize()
+    wall_ms = (time.perf_counter() - t0) * 1e3
+    ms_per_step = wall_ms / args.steps
+    ev_ms_per_step = e0.elapsed_time(e1) / args.steps
+
+    # ---- second pass: HIP events around every launch (same stream, same inputs)
+    n_prof = min(args.steps, 20)
+    prof = B.KernelProfile(32 * n_prof)
+    with prof:
+        for i in range(n_prof):
+            step(i)
+    durs = prof.durations_ms()
+    per_step = len(durs) // n_prof
+    names = [n for n, _ in durs[:per_step]]
+    avg_ms = [sum(durs[j * per_step + i][1] for j in range(n_prof)) / n_prof for i in range(per_step)]
+    models = kernel_models(wl, lens)
+    kernels = []
+    mi = 0
+    for n, ms in zip(names, avg_ms):
+        fam = FAMILY_OF_LAUNCH.get(n)
+        entry = {"launch": n, "avg_us": round(ms * 1e3, 2)}
+        if fam is not None and mi < len(models) and models[mi][0] == fam:
+            _, label, nbytes, flops = models[mi]
+            mi += 1
+            entry.update({"step": label, "algo_bytes": int(nbytes), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                          "hbm_frac": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)})
+            if flops:
+                entry["TFLOPs"] = round(flops / (ms * 1e-3) / 1e12, 2)
+                entry["mfma_frac"] = round(flops / (ms * 1e-3) / 1e12 / MFMA_BF16_PEAK_TFLOPS, 4)
+        kernels.append(entry)
+    timed = [k for k in kernels if "algo_bytes" in k]
+    dom = max(timed, key=lambda k: k["avg_us"])
+    mfma_bound = dom.get("mfma_frac", 0) > dom["hbm_frac"]
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "hbm_traffic.json")
+    if os.path.exists(tpath):
+        try:
+            traffic = json.load(open(tpath)).get(args.workload, {}).get(dom["launch"])
+        except Exception:
+            traffic = None
+    if mfma_bound:
+        roofline = {"bound": "mfma", "achieved": dom["TFLOPs"], "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                    "frac": dom["mfma_frac"], "traffic": traffic, "kernel": dom["launch"], "step": dom["step"],
+                    "avg_us": dom["avg_us"]}
+    else:
+        roofline = {"bound": "hbm", "achieved": dom["GBps"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                    "frac": dom["hbm_frac"], "traffic": traffic, "kernel": dom["launch"], "step": dom["step"],
+                    "avg_us": dom["avg_us"], "algo_bytes": dom["algo_bytes"]}
+
+    result = {
+        "metric": "decode-layer tokens/s at 1 MI355X", "value": round(T / (ms_per_step * 1e-3), 1), "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5),
+        "event_ms_per_step": round(ev_ms_per_step, 5), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": f"{wl.name}: H={s.H} heads={s.nq}/{s.nkv} d={s.d} F={s.F} E={s.E} k={s.k} mode={wl.mode} "
+                               f"batch={wl.B} tokens={T} ctx={'ragged' if wl.ctx_range else (wl.ctx or wl.seq_tokens)}",
+                   "tokens_per_step": T, "kv_copies_rotated": len(sets), "setup_s": round(setup_s, 1)},
+        "roofline": roofline,
+        "sum_kernel_us": round(sum(k["avg_us"] for k in kernels), 1),
+        "kernels": kernels,
+    }
+
+    if not args.no_cpu_baseline:
+        from oracle import decoder_layer as O
+        try:
+            from threadpoolctl import threadpool_info
+            nthreads = max([p.get("num_threads", 1) for p in threadpool_info()] or [1])
+        except Exception:
+            nthreads = len(os.sched_getaffinity(0))
+        # bounded sample: the whole layer once if small, else a subset of sequences/tokens
+        w64 = {k: WL.as_f64(v) for k, v in weights.items()}
+        if wl.mode == "decode":
+            nb = Bs if args.workload in ("tiny", "8b_decode") else min(Bs, 16)
+            io_o = {k: (v[:nb] if k != "seq_id" else v[:nb]) for k, v in io.items()}
+            io_o = {k: (WL.as_f32(v) if k in ("kcache", "vcache") else WL.as_f64(v)) for k, v in io_o.items()}
+            sample = f"full layer, {nb} of {Bs} sequences, once"
+            ntok = nb
+        else:
+            n1 = lens[0]
+            io_o = {"x": WL.as_f64(io["x"][:n1]), "pos": WL.as_f64(io["pos"][:n1]), "seq_id": WL.as_f64(io["seq_id"][:n1]),
+                    "cu_seqlens": np.array([0, n1]), "kcache": WL.as_f32(io["kcache"][:1]), "vcache": WL.as_f32(io["vcache"][:1])}
+            sample = f"full layer, first sequence ({n1} tokens) of {Bs}, once"
+            ntok = n1
+        t0 = time.perf_counter()
+        ref = O.layer_forward(s, w64, io_o, wl.mode)
+        cpu_s = time.perf_counter() - t0
+        got = sets[(args.steps - 1) % len(sets)][2][:ntok].float().cpu().numpy().astype(np.float64)
+        diff = got - ref["out"]
+        result["cpu_baseline"] = {"value": round(ntok / cpu_s, 2), "unit": "tokens/s", "cores": int(nthreads),
+                                  "kind": "oracle", "sample": sample + f" ({cpu_s:.1f} s; numpy fp64, BLAS threads={nthreads}, "
+                                  "attention loops single-threaded)"}
+        if s.E == 0:
+            result["parity_vs_oracle"] = {"max_abs": float(np.abs(diff).max()),
+                                          "rel_l2": float(np.linalg.norm(diff) / np.linalg.norm(ref["out"]))}
+    print(json.dumps(result))
+
+
+if __name__ == "__main__":
+    main()

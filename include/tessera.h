@@ -61,6 +61,21 @@ const char* ts_last_error(void);
 const char* ts_version(void);
 
 /* ---------------------------------------------------------------------------
+ * Per-kernel latency profile (the t_{k,g} table the policy planner of Sec. 3.2
+ * is fed with, measured per launch).  Between ts_profile_begin and
+ * ts_profile_end every kernel the calling thread launches through this library
+ * is bracketed by two of the caller's events, recorded on the launch stream:
+ * events[2*i] before launch i, events[2*i+1] after it; names[i] receives a
+ * pointer to a static kernel-family name.  events: HOST array of 2*max_launches
+ * hipEvent_t created with timing enabled; names: HOST array of max_launches
+ * pointers.  Launches beyond max_launches are not recorded.  ts_profile_end
+ * returns the number of recorded launches (>= 0) and deactivates the profile;
+ * the caller synchronises and reads elapsed times itself.
+ */
+int ts_profile_begin(void** events, const char** names, int max_launches);
+int ts_profile_end(void);
+
+/* ---------------------------------------------------------------------------
  * RMSNorm: y[t,i] = x[t,i] * rsqrt(mean_j x[t,j]^2 + eps) * gamma[i].
  * One of the small memory-bound kernels of the layer (Sec. 2.3 regime split).
  * x, y: [T,H]; gamma: [H].  y may alias x.  Requires H % 8 == 0, H <= 32768.

@@ -21,7 +21,7 @@ TS_B_OUT_DENSE, TS_NB_DENSE = 7, 8
 TS_B_Y_MOE, TS_B_OUT_MOE, TS_NB_MOE = 7, 8, 9
 
 EXPORTS = [
-    "ts_strerror", "ts_last_error", "ts_version", "ts_rmsnorm", "ts_gemm_workspace_bytes", "ts_gemm_bf16",
+    "ts_strerror", "ts_last_error", "ts_version", "ts_profile_begin", "ts_profile_end", "ts_rmsnorm", "ts_gemm_workspace_bytes", "ts_gemm_bf16",
     "ts_gemm_bf16_f32out", "ts_rope", "ts_rope_table", "ts_attention_decode_workspace_bytes",
     "ts_attention_decode", "ts_attention_prefill", "ts_swiglu", "ts_moe_route", "ts_moe_gemm", "ts_moe_combine",
     "ts_layer_workspace_bytes", "ts_layer_boundary", "ts_layer_moe_buffers", "ts_layer_forward",
@@ -70,6 +70,8 @@ lib = _load()
 
 _i, _f, _p, _z, _u64 = C.c_int, C.c_float, C.c_void_p, C.c_size_t, C.c_uint64
 lib.ts_strerror.argtypes = [_i]
+lib.ts_profile_begin.argtypes = [C.POINTER(_p), C.POINTER(C.c_char_p), _i]
+lib.ts_profile_end.argtypes = []
 lib.ts_rmsnorm.argtypes = [_p, _p, _p, _i, _i, _f, _p]
 lib.ts_gemm_workspace_bytes.argtypes = [_i, _i, _i]
 lib.ts_gemm_bf16.argtypes = [_p, _p, _p, _p, _i, _i, _i, _p, _z, _p]
@@ -264,3 +266,34 @@ def ts_pipeline_step(handle: int, weights: LayerWeights, mbs: Sequence[LayerIO],
     _check(lib.ts_pipeline_step(handle, C.byref(weights), arr, len(mbs), cs, _stream(copy_stream),
                                 mask & (2 ** 64 - 1), 1 if copy_on_compute_stream else 0, _ptr(dev_staging),
                                 _ptr(pinned_host), _nbytes(dev_staging), _ptr(ws), _nbytes(ws)))
+
+
+class KernelProfile:
+    """Brackets every library launch on this thread with a pair of timing events.
+
+    with KernelProfile(max_launches) as prof: ...calls...; then prof.durations_ms() after a sync
+    returns [(kernel_family_name, milliseconds), ...] in launch order.
+    """
+
+    def __init__(self, max_launches: int):
+        self.cap = max_launches
+        self.events = [torch.cuda.Event(enable_timing=True) for _ in range(2 * max_launches)]
+        for e in self.events:          # torch creates the HIP event lazily, on the first record
+            e.record()
+        torch.cuda.synchronize()
+        self._ev = (_p * (2 * max_launches))(*[e.cuda_event for e in self.events])
+        self._names = (C.c_char_p * max_launches)()
+        self.n = 0
+
+    def __enter__(self):
+        _check(lib.ts_profile_begin(self._ev, self._names, self.cap))
+        return self
+
+    def __exit__(self, *exc):
+        self.n = lib.ts_profile_end()
+        return False
+
+    def durations_ms(self):
+        torch.cuda.synchronize()
+        return [(self._names[i].decode(), self.events[2 * i].elapsed_time(self.events[2 * i + 1]))
+                for i in range(self.n)]

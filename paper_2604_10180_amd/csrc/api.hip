@@ -32,6 +32,26 @@ int check_hip(hipError_t e, const char* what) {
   return TS_ERR_HIP;
 }
 
+// ---- per-launch profile (thread-local; events belong to the caller) ----------
+struct Profile {
+  hipEvent_t* events = nullptr;   // pairs: [2*i] before, [2*i+1] after launch i
+  const char** names = nullptr;
+  int cap = 0, used = 0;
+  bool active = false;
+};
+static thread_local Profile g_prof;
+
+void prof_begin(const char* name, hipStream_t s) {
+  if (!g_prof.active || g_prof.used >= g_prof.cap) return;
+  g_prof.names[g_prof.used] = name;
+  (void)hipEventRecord(g_prof.events[2 * g_prof.used], s);
+}
+void prof_end(hipStream_t s) {
+  if (!g_prof.active || g_prof.used >= g_prof.cap) return;
+  (void)hipEventRecord(g_prof.events[2 * g_prof.used + 1], s);
+  ++g_prof.used;
+}
+
 namespace {
 
 inline hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
@@ -241,6 +261,23 @@ const char* ts_strerror(int code) {
 }
 const char* ts_last_error(void) { return g_err; }
 const char* ts_version(void) { return "tessera-mi355x 0.1 (gfx950)"; }
+
+int ts_profile_begin(void** events, const char** names, int max_launches) {
+  TS_REQUIRE(events != nullptr && names != nullptr && max_launches > 0, TS_ERR_INVALID_ARG,
+             "ts_profile_begin: bad arguments");
+  g_prof.events = reinterpret_cast<hipEvent_t*>(events);
+  g_prof.names = names;
+  g_prof.cap = max_launches;
+  g_prof.used = 0;
+  g_prof.active = true;
+  return TS_OK;
+}
+
+int ts_profile_end(void) {
+  const int n = g_prof.active ? g_prof.used : 0;
+  g_prof = Profile();
+  return n;
+}
 
 int ts_rmsnorm(const ts_bf16* x, const ts_bf16* gamma, ts_bf16* y, int T, int H, float eps, void* stream) {
   TS_REQUIRE(T >= 0 && H > 0, TS_ERR_INVALID_ARG, "ts_rmsnorm: T=%d H=%d", T, H);

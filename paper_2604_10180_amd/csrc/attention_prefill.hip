@@ -152,11 +152,11 @@ int launch_attention_prefill(const ts_bf16* q, const ts_bf16* k, const ts_bf16* 
   dim3 grid(cdiv(max_seqlen, 64), nq, S);
   if (d == 128) {
     const size_t smem = (size_t)4 * 32 * 17 * sizeof(uint4);
-    hipLaunchKernelGGL(attn_prefill_kernel<128>, grid, dim3(256), smem, s, q, k, v, q_stride, kv_stride, cu, out, nq,
+    TS_LAUNCH("attn_prefill", attn_prefill_kernel<128>, grid, dim3(256), smem, s, q, k, v, q_stride, kv_stride, cu, out, nq,
                        nkv, c_scale, causal);
   } else {
     const size_t smem = (size_t)4 * 32 * 9 * sizeof(uint4);
-    hipLaunchKernelGGL(attn_prefill_kernel<64>, grid, dim3(256), smem, s, q, k, v, q_stride, kv_stride, cu, out, nq,
+    TS_LAUNCH("attn_prefill", attn_prefill_kernel<64>, grid, dim3(256), smem, s, q, k, v, q_stride, kv_stride, cu, out, nq,
                        nkv, c_scale, causal);
   }
   TS_LAUNCH_CHECK("attn_prefill");

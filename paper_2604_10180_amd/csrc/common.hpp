@@ -26,6 +26,18 @@ int check_hip(hipError_t e, const char* what);
 // checks the launch that was just issued
 #define TS_LAUNCH_CHECK(name) TS_HIP(hipGetLastError())
 
+// Optional per-launch timing: when a profile is active on the calling thread, every kernel
+// launch is bracketed by two caller-supplied events recorded on the launch stream.
+void prof_begin(const char* name, hipStream_t s);
+void prof_end(hipStream_t s);
+
+#define TS_LAUNCH(name, kernel, grid, block, smem, stream, ...)                  \
+  do {                                                                           \
+    ::ts::prof_begin(name, stream);                                              \
+    hipLaunchKernelGGL(kernel, grid, block, smem, stream, __VA_ARGS__);          \
+    ::ts::prof_end(stream);                                                      \
+  } while (0)
+
 static inline bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 static inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
 static inline int cdiv(int a, int b) { return (a + b - 1) / b; }
@@ -60,6 +72,14 @@ __device__ __forceinline__ uint16_t f_to_bf(float f) {
 }
 
 __device__ __forceinline__ uint4 ldg16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
+// Predicated 16-byte load without a branch: `p` must be a readable address even when !ok
+// (callers clamp it); the result is zeroed when !ok.  (A conditional expression around a
+// 16-byte load is split by the compiler into four branchy 4-byte loads.)
+__device__ __forceinline__ uint4 ldg16_or_zero(const void* p, bool ok) {
+  uint4 v = *reinterpret_cast<const uint4*>(p);
+  v.x = ok ? v.x : 0u; v.y = ok ? v.y : 0u; v.z = ok ? v.z : 0u; v.w = ok ? v.w : 0u;
+  return v;
+}
 __device__ __forceinline__ void stg16(void* p, uint4 v) { *reinterpret_cast<uint4*>(p) = v; }
 
 __device__ __forceinline__ float wave_sum(float v) {

@@ -60,11 +60,11 @@ int launch_rmsnorm(const ts_bf16* x, const ts_bf16* gamma, ts_bf16* y, int T, in
   const uint4* gp = reinterpret_cast<const uint4*>(gamma);
   uint4* yp = reinterpret_cast<uint4*>(y);
   const float inv_h = 1.0f / (float)H;
-  if (vpt <= 1) hipLaunchKernelGGL(rmsnorm_kernel<1>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h);
-  else if (vpt <= 2) hipLaunchKernelGGL(rmsnorm_kernel<2>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h);
-  else if (vpt <= 4) hipLaunchKernelGGL(rmsnorm_kernel<4>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h);
-  else if (vpt <= 8) hipLaunchKernelGGL(rmsnorm_kernel<8>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h);
-  else hipLaunchKernelGGL(rmsnorm_kernel<16>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h);
+  if (vpt <= 1) TS_LAUNCH("rmsnorm", rmsnorm_kernel<1>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h);
+  else if (vpt <= 2) TS_LAUNCH("rmsnorm", rmsnorm_kernel<2>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h);
+  else if (vpt <= 4) TS_LAUNCH("rmsnorm", rmsnorm_kernel<4>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h);
+  else if (vpt <= 8) TS_LAUNCH("rmsnorm", rmsnorm_kernel<8>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h);
+  else TS_LAUNCH("rmsnorm", rmsnorm_kernel<16>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h);
   TS_LAUNCH_CHECK("rmsnorm");
   return TS_OK;
 }
@@ -95,7 +95,7 @@ int launch_swiglu(const ts_bf16* gu, ts_bf16* out, int T, int F, hipStream_t s) 
   const int F8 = F / 8;
   long total = (long)T * F8;
   dim3 grid((unsigned)((total + 255) / 256)), block(256);
-  hipLaunchKernelGGL(swiglu_kernel, grid, block, 0, s, reinterpret_cast<const uint4*>(gu),
+  TS_LAUNCH("swiglu", swiglu_kernel, grid, block, 0, s, reinterpret_cast<const uint4*>(gu),
                      reinterpret_cast<uint4*>(out), total, F8);
   TS_LAUNCH_CHECK("swiglu");
   return TS_OK;
@@ -175,7 +175,7 @@ int launch_rope(ts_bf16* q, ts_bf16* k, const ts_bf16* v, int q_stride, int kv_s
   if (T == 0) return TS_OK;
   const int items = (nq + nkv) * (d / 16) + (vcache ? nkv * (d / 8) : 0);
   dim3 grid(cdiv(items, 256), T), block(256);
-  hipLaunchKernelGGL(rope_kernel, grid, block, 0, s, q, k, v, q_stride, kv_stride, pos, seq_id, cos_sin, table_len,
+  TS_LAUNCH("rope", rope_kernel, grid, block, 0, s, q, k, v, q_stride, kv_stride, pos, seq_id, cos_sin, table_len,
                      kcache, vcache, nq, nkv, d, Lcap, base);
   TS_LAUNCH_CHECK("rope");
   return TS_OK;
@@ -193,7 +193,7 @@ int launch_copy16(const void* src, void* dst, size_t bytes, hipStream_t s) {
   size_t n16 = bytes / 16;
   unsigned blocks = (unsigned)((n16 + 255) / 256);
   if (blocks > 2048) blocks = 2048;
-  hipLaunchKernelGGL(copy16_kernel, dim3(blocks), dim3(256), 0, s, reinterpret_cast<const uint4*>(src),
+  TS_LAUNCH("copy16", copy16_kernel, dim3(blocks), dim3(256), 0, s, reinterpret_cast<const uint4*>(src),
                      reinterpret_cast<uint4*>(dst), n16);
   TS_LAUNCH_CHECK("copy16");
   return TS_OK;

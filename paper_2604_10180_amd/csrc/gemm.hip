@@ -68,15 +68,14 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs a) {
   for (int m0 = 0; m0 < Mtot; m0 += ROWS) {
     const int Mcur = min(ROWS, Mtot - m0);
     const ts_bf16* arow[MT];
+    bool avalid[MT];
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
-      int r = st_r + 16 * i;
-      long src = 0;
-      if (r < Mcur) {
-        src = (long)row0 + m0 + r;
-        if (a.row_map != nullptr) src = a.row_map[src] / a.row_div;
-      }
-      arow[i] = (r < Mcur) ? a.A + (size_t)src * K : nullptr;
+      const int r = st_r + 16 * i;
+      avalid[i] = r < Mcur;
+      long src = (long)row0 + m0 + (avalid[i] ? r : 0);   // rows past the end re-read row 0, zeroed
+      if (a.row_map != nullptr) src = a.row_map[src] / a.row_div;
+      arow[i] = a.A + (size_t)src * K;
     }
     f32x4 acc[MT][NT];
 #pragma unroll
@@ -85,22 +84,23 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs a) {
       for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     U4 wreg[NT][4], wnext[NT][4], areg[MT];
-    const uint4 zero4 = make_uint4(0, 0, 0, 0);
 
     auto load_w = [&](int k0, U4(&dst)[NT][4]) {
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          int k = k0 + (j * 4 + g) * 8;
-          dst[nt][j].u = (k < kend) ? ldg16(wrow[nt] + k) : zero4;
+          const int k = k0 + (j * 4 + g) * 8;
+          const bool ok = k < kend;
+          dst[nt][j].u = ldg16_or_zero(wrow[nt] + (ok ? k : kbeg), ok);
         }
     };
     auto load_a = [&](int k0) {
 #pragma unroll
       for (int i = 0; i < MT; ++i) {
-        int k = k0 + st_c * 8;
-        areg[i].u = (arow[i] != nullptr && k < kend) ? ldg16(arow[i] + k) : zero4;
+        const int k = k0 + st_c * 8;
+        const bool ok = avalid[i] && k < kend;
+        areg[i].u = ldg16_or_zero(arow[i] + (ok ? k : kbeg), ok);
       }
     };
     auto store_a = [&](int buf) {
@@ -108,17 +108,23 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs a) {
       for (int i = 0; i < MT; ++i) lds[buf][st_r + 16 * i][st_c] = areg[i].u;
     };
 
-    load_w(kbeg, wreg);
-    load_a(kbeg);
+    // Workgroups start their K walk at different slabs (and wrap around): all of them
+    // walking k = 0,128,... in step would keep hitting the same few HBM channels, because
+    // rows are a power-of-two stride apart.
+    const int niter = (kend - kbeg + 127) / 128;
+    const int rot = (int)((blockIdx.x * 7u + blockIdx.z * 3u) % (unsigned)niter);
+    auto slab = [&](int it) { int r = it + rot; return kbeg + (r >= niter ? r - niter : r) * 128; };
+    load_w(slab(0), wreg);
+    load_a(slab(0));
     store_a(0);
     __syncthreads();
-    int it = 0;
-    for (int k0 = kbeg; k0 < kend; k0 += 128, ++it) {
+    for (int it = 0; it < niter; ++it) {
       const int cur = it & 1;
-      const bool more = (k0 + 128) < kend;
+      const bool more = (it + 1) < niter;
       if (more) {
-        load_w(k0 + 128, wnext);
-        load_a(k0 + 128);
+        const int kn = slab(it + 1);
+        load_w(kn, wnext);
+        load_a(kn);
       }
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
@@ -260,13 +266,13 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const ts_bf16* __restri
       for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
 
   uint4 wr[LW], ar[LA];
-  const uint4 zero4 = make_uint4(0, 0, 0, 0);
   auto gload = [&](int k0) {
     const bool ok = (k0 + st_c * 8) < K;
+    const int kk = ok ? k0 : 0;
 #pragma unroll
-    for (int i = 0; i < LW; ++i) wr[i] = ok ? ldg16(wptr[i] + k0) : zero4;
+    for (int i = 0; i < LW; ++i) wr[i] = ldg16_or_zero(wptr[i] + kk, ok);
 #pragma unroll
-    for (int i = 0; i < LA; ++i) ar[i] = ok ? ldg16(aptr[i] + k0) : zero4;
+    for (int i = 0; i < LA; ++i) ar[i] = ldg16_or_zero(aptr[i] + kk, ok);
   };
   auto sstore = [&](int buf) {
 #pragma unroll
@@ -387,10 +393,10 @@ void launch_skinny_mt(const SkinnyArgs& a, int NT, dim3 grid, hipStream_t s) {
   const size_t smem = (size_t)2 * MT * 16 * 17 * sizeof(uint4);
   if (NT == 2) {
     allow_lds(gemm_skinny_kernel<MT, 2, GROUPED>, smem);
-    hipLaunchKernelGGL((gemm_skinny_kernel<MT, 2, GROUPED>), grid, dim3(256), smem, s, a);
+    TS_LAUNCH("gemm_skinny", (gemm_skinny_kernel<MT, 2, GROUPED>), grid, dim3(256), smem, s, a);
   } else {
     allow_lds(gemm_skinny_kernel<MT, 1, GROUPED>, smem);
-    hipLaunchKernelGGL((gemm_skinny_kernel<MT, 1, GROUPED>), grid, dim3(256), smem, s, a);
+    TS_LAUNCH("gemm_skinny", (gemm_skinny_kernel<MT, 1, GROUPED>), grid, dim3(256), smem, s, a);
   }
 }
 
@@ -427,7 +433,7 @@ int launch_gemm(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, voi
     TS_LAUNCH_CHECK("gemm_skinny");
     if (p.S > 1) {
       long MN = (long)M * N;
-      hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((MN / 2 + 255) / 256)), dim3(256), 0, s,
+      TS_LAUNCH("splitk_reduce", splitk_reduce_kernel, dim3((unsigned)((MN / 2 + 255) / 256)), dim3(256), 0, s,
                          reinterpret_cast<const float*>(ws), residual, C, MN, p.S, f32out ? 1 : 0);
       TS_LAUNCH_CHECK("splitk_reduce");
     }
@@ -439,10 +445,10 @@ int launch_gemm(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, voi
   dim3 grid(tiles_m * tiles_n);
   if (f32out) {
     allow_lds(gemm_tiled_kernel<BM, BN, true>, smem);
-    hipLaunchKernelGGL((gemm_tiled_kernel<BM, BN, true>), grid, dim3(256), smem, s, A, W, residual, C, M, N, K, tiles_m);
+    TS_LAUNCH("gemm_tiled", (gemm_tiled_kernel<BM, BN, true>), grid, dim3(256), smem, s, A, W, residual, C, M, N, K, tiles_m);
   } else {
     allow_lds(gemm_tiled_kernel<BM, BN, false>, smem);
-    hipLaunchKernelGGL((gemm_tiled_kernel<BM, BN, false>), grid, dim3(256), smem, s, A, W, residual, C, M, N, K, tiles_m);
+    TS_LAUNCH("gemm_tiled", (gemm_tiled_kernel<BM, BN, false>), grid, dim3(256), smem, s, A, W, residual, C, M, N, K, tiles_m);
   }
   TS_LAUNCH_CHECK("gemm_tiled");
   return TS_OK;

@@ -79,10 +79,10 @@ __global__ __launch_bounds__(256) void moe_group_kernel(const int32_t* __restric
 int launch_moe_route(const float* logits, int T, int E, int k, int32_t* idx, float* w, int32_t* counts,
                      int32_t* offsets, int32_t* perm, hipStream_t s) {
   if (T > 0) {
-    hipLaunchKernelGGL(moe_topk_kernel, dim3(cdiv(T, 256)), dim3(256), 0, s, logits, T, E, k, idx, w);
+    TS_LAUNCH("moe_topk", moe_topk_kernel, dim3(cdiv(T, 256)), dim3(256), 0, s, logits, T, E, k, idx, w);
     TS_LAUNCH_CHECK("moe_topk");
   }
-  hipLaunchKernelGGL(moe_group_kernel, dim3(E), dim3(256), 0, s, idx, T * k, E, counts, offsets, perm);
+  TS_LAUNCH("moe_group", moe_group_kernel, dim3(E), dim3(256), 0, s, idx, T * k, E, counts, offsets, perm);
   TS_LAUNCH_CHECK("moe_group");
   return TS_OK;
 }
@@ -133,11 +133,11 @@ int launch_moe_combine(const ts_bf16* y, const int32_t* perm, const float* w, co
                        int32_t* inv, int T, int k, int H, hipStream_t s) {
   if (T == 0) return TS_OK;
   int n = T * k;
-  hipLaunchKernelGGL(moe_invert_kernel, dim3(cdiv(n, 256)), dim3(256), 0, s, perm, inv, n);
+  TS_LAUNCH("moe_invert", moe_invert_kernel, dim3(cdiv(n, 256)), dim3(256), 0, s, perm, inv, n);
   TS_LAUNCH_CHECK("moe_invert");
   const int H8 = H / 8;
   long total = (long)T * H8;
-  hipLaunchKernelGGL(moe_combine_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+  TS_LAUNCH("moe_combine", moe_combine_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
                      reinterpret_cast<const uint4*>(y), inv, w, reinterpret_cast<const uint4*>(residual),
                      reinterpret_cast<uint4*>(out), total, H8, k);
   TS_LAUNCH_CHECK("moe_combine");
