@@ -10,6 +10,7 @@
 // token row and stores 8 contiguous bytes.  Both operands are K-contiguous in memory, so a
 // lane's 8-element operand fragment is one 16-byte load; which 8 k-values a lane group
 // holds is free as long as both operands agree, and is chosen for contiguous loads.
+#include <type_traits>
 #include "common.hpp"
 
 namespace ts {
@@ -68,12 +69,10 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs a) {
   for (int m0 = 0; m0 < Mtot; m0 += ROWS) {
     const int Mcur = min(ROWS, Mtot - m0);
     const ts_bf16* arow[MT];
-    bool avalid[MT];
 #pragma unroll
     for (int i = 0; i < MT; ++i) {
       const int r = st_r + 16 * i;
-      avalid[i] = r < Mcur;
-      long src = (long)row0 + m0 + (avalid[i] ? r : 0);   // rows past the end re-read row 0, zeroed
+      long src = (long)row0 + m0 + (r < Mcur ? r : 0);   // rows past the end re-read row 0
       if (a.row_map != nullptr) src = a.row_map[src] / a.row_div;
       arow[i] = a.A + (size_t)src * K;
     }
@@ -83,9 +82,23 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs a) {
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    U4 wreg[NT][4], wnext[NT][4], areg[MT];
+    // Three-stage ring, prefetch distance 2: while slab `it` is multiplied, the W fragments
+    // of slabs it+1 and it+2 are in flight in registers and the activation slab it+1 moves
+    // from registers to LDS.  One barrier per slab; barriers wait on LDS only, never on the
+    // outstanding global loads.
+    U4 wbuf[3][NT][4], areg[MT];
 
+    // Rows past the end of A or W are clamped to a valid row: they only feed output elements
+    // that are never stored.  Only a K tail (K % 128 != 0) needs zeros, and zeroing the W
+    // fragment is enough (the matching A chunk is re-read from the last valid chunk of the
+    // same row).  Full slabs use unpredicated loads so nothing consumes a load at issue time.
     auto load_w = [&](int k0, U4(&dst)[NT][4]) {
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) dst[nt][j].u = ldg16(wrow[nt] + k0 + (j * 4 + g) * 8);
+    };
+    auto load_w_tail = [&](int k0, U4(&dst)[NT][4]) {
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
@@ -96,56 +109,80 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs a) {
         }
     };
     auto load_a = [&](int k0) {
+      const int k = min(k0 + st_c * 8, kend - 8);
 #pragma unroll
-      for (int i = 0; i < MT; ++i) {
-        const int k = k0 + st_c * 8;
-        const bool ok = avalid[i] && k < kend;
-        areg[i].u = ldg16_or_zero(arow[i] + (ok ? k : kbeg), ok);
-      }
+      for (int i = 0; i < MT; ++i) areg[i].u = ldg16(arow[i] + k);
     };
     auto store_a = [&](int buf) {
 #pragma unroll
       for (int i = 0; i < MT; ++i) lds[buf][st_r + 16 * i][st_c] = areg[i].u;
     };
-
-    // Workgroups start their K walk at different slabs (and wrap around): all of them
-    // walking k = 0,128,... in step would keep hitting the same few HBM channels, because
-    // rows are a power-of-two stride apart.
-    const int niter = (kend - kbeg + 127) / 128;
-    const int rot = (int)((blockIdx.x * 7u + blockIdx.z * 3u) % (unsigned)niter);
-    auto slab = [&](int it) { int r = it + rot; return kbeg + (r >= niter ? r - niter : r) * 128; };
-    load_w(slab(0), wreg);
-    load_a(slab(0));
-    store_a(0);
-    __syncthreads();
-    for (int it = 0; it < niter; ++it) {
-      const int cur = it & 1;
-      const bool more = (it + 1) < niter;
-      if (more) {
-        const int kn = slab(it + 1);
-        load_w(kn, wnext);
-        load_a(kn);
-      }
+    auto compute = [&](int buf, U4(&w)[NT][4]) {
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) {
-          if (mt * 16 < Mcur) {
-            U4 b;
-            b.u = lds[cur][mt * 16 + l16][j * 4 + g];
+          U4 b;
+          b.u = lds[buf][mt * 16 + l16][j * 4 + g];
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-              acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wreg[nt][j].b, b.b, acc[mt][nt], 0, 0, 0);
-          }
+          for (int nt = 0; nt < NT; ++nt)
+            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[nt][j].b, b.b, acc[mt][nt], 0, 0, 0);
         }
       }
-      if (more) {
-        store_a(cur ^ 1);
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt)
-#pragma unroll
-          for (int j = 0; j < 4; ++j) wreg[nt][j] = wnext[nt][j];
+    };
+
+    // Full 128-wide slabs run through the ring.  Workgroups start their K walk at different
+    // slabs (and wrap around), so that they do not all sweep the same activation addresses
+    // and the same HBM channels in step.
+    const int nfull = (kend - kbeg) / 128;
+    if (nfull > 0) {
+      const int rot = (int)((blockIdx.x * 7u + blockIdx.z * 3u) % (unsigned)nfull);
+      auto slab = [&](int it) { int r = it + rot; return kbeg + (r >= nfull ? r - nfull : r) * 128; };
+      // one ring step; CHECKED = false is the branch-free steady state
+      auto step = [&](auto checked, auto stage, int it) {
+        constexpr bool CHECKED = decltype(checked)::value;
+        constexpr int u = decltype(stage)::value;
+        if (!CHECKED || it + 1 < nfull) store_a((u + 1) % 3);
+        if (!CHECKED || it + 2 < nfull) {
+          const int kn = slab(it + 2);
+          load_a(kn);
+          load_w(kn, wbuf[(u + 2) % 3]);
+        }
+        compute(u, wbuf[u]);
+        __syncthreads();
+      };
+      using T_ = std::true_type;
+      using F_ = std::false_type;
+      using S0 = std::integral_constant<int, 0>;
+      using S1 = std::integral_constant<int, 1>;
+      using S2 = std::integral_constant<int, 2>;
+      load_a(slab(0));
+      load_w(slab(0), wbuf[0]);
+      store_a(0);
+      if (nfull > 1) {
+        load_a(slab(1));
+        load_w(slab(1), wbuf[1]);
       }
+      __syncthreads();
+      int it = 0;
+      for (; it + 4 < nfull; it += 3) {
+        step(F_{}, S0{}, it);
+        step(F_{}, S1{}, it + 1);
+        step(F_{}, S2{}, it + 2);
+      }
+      for (; it < nfull; it += 3) {
+        step(T_{}, S0{}, it);
+        if (it + 1 < nfull) step(T_{}, S1{}, it + 1);
+        if (it + 2 < nfull) step(T_{}, S2{}, it + 2);
+      }
+    }
+    if (kbeg + nfull * 128 < kend) {   // K tail: one partial slab, not pipelined
+      const int kt = kbeg + nfull * 128;
+      load_a(kt);
+      load_w_tail(kt, wbuf[0]);
+      store_a(0);
+      __syncthreads();
+      compute(0, wbuf[0]);
       __syncthreads();
     }
 
@@ -390,7 +427,7 @@ void allow_lds(KernelT kernel, size_t bytes) {
 
 template <int MT, bool GROUPED>
 void launch_skinny_mt(const SkinnyArgs& a, int NT, dim3 grid, hipStream_t s) {
-  const size_t smem = (size_t)2 * MT * 16 * 17 * sizeof(uint4);
+  const size_t smem = (size_t)3 * MT * 16 * 17 * sizeof(uint4);
   if (NT == 2) {
     allow_lds(gemm_skinny_kernel<MT, 2, GROUPED>, smem);
     TS_LAUNCH("gemm_skinny", (gemm_skinny_kernel<MT, 2, GROUPED>), grid, dim3(256), smem, s, a);
