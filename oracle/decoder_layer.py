@@ -114,11 +114,12 @@ def attention_decode(q: np.ndarray, kcache: np.ndarray, vcache: np.ndarray,
         L = int(seq_lens[b])
         if L <= 0:
             continue                      # no key: output defined as zero
-        for h in range(nq):
-            K = np.asarray(kcache[b, h // g, :L, :], F64)
-            V = np.asarray(vcache[b, h // g, :L, :], F64)
-            s = scale * (K @ q[b, h])
-            out[b, h] = _softmax_av(s, V)
+        for kvh in range(nkv):
+            K = np.asarray(kcache[b, kvh, :L, :], F64)     # widened once per kv head
+            V = np.asarray(vcache[b, kvh, :L, :], F64)
+            for h in range(kvh * g, (kvh + 1) * g):        # the g query heads that share it
+                s = scale * (K @ q[b, h])
+                out[b, h] = _softmax_av(s, V)
     return out
 
 
