@@ -118,16 +118,18 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs a) {
       for (int i = 0; i < MT; ++i) lds[buf][st_r + 16 * i][st_c] = areg[i].u;
     };
     auto compute = [&](int buf, U4(&w)[NT][4]) {
+      // read a whole k-step of activation fragments before the MFMAs that use them, so the
+      // LDS latency is paid once per step instead of once per MFMA
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
+        U4 b[MT];
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt) {
-          U4 b;
-          b.u = lds[buf][mt * 16 + l16][j * 4 + g];
+        for (int mt = 0; mt < MT; ++mt) b[mt].u = lds[buf][mt * 16 + l16][j * 4 + g];
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
           for (int nt = 0; nt < NT; ++nt)
-            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[nt][j].b, b.b, acc[mt][nt], 0, 0, 0);
-        }
+            acc[mt][nt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(w[nt][j].b, b[mt].b, acc[mt][nt], 0, 0, 0);
       }
     };
 
@@ -400,7 +402,7 @@ SkinnyPlan plan_skinny(int N, int K) {
   SkinnyPlan p;
   const int t2 = cdiv(N, 128), t1 = cdiv(N, 64);
   p.S = 1;
-  if (t2 >= 448) {
+  if (t2 >= 192) {   // enough 128-row workgroups: halves the activation re-reads from L2
     p.NT = 2;
   } else {
     p.NT = 1;
