@@ -274,7 +274,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 template <int BM, int BN, bool F32OUT>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(const ts_bf16* __restrict__ A, const ts_bf16* __restrict__ W,
                                                          const ts_bf16* __restrict__ residual, void* __restrict__ C,
-                                                         int M, int N, int K, int tiles_m) {
+                                                         int M, int N, int K, int tiles_m, int tiles_n) {
   constexpr int TN = BN / 64, TM = BM / 64;
   constexpr int LW = BN / 32, LA = BM / 32;  // 16-byte chunks per thread per tile
   extern __shared__ uint4 smem[];
@@ -285,7 +285,18 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const ts_bf16* __restri
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r32 = lane & 31, g = lane >> 5;
   const int wn = wave & 1, wm = wave >> 1;
-  const int tile_m = blockIdx.x % tiles_m, tile_n = blockIdx.x / tiles_m;
+  // Workgroup -> tile.  Consecutive workgroup ids go round-robin to the 8 XCDs (each with its
+  // own L2), so ids are first regrouped so that an XCD works on a contiguous run of logical
+  // tiles; logical tiles walk groups of 8 row tiles down the columns, so the ~32 tiles an XCD
+  // runs at a time form an 8 x 4 patch that shares operand tiles in that L2.
+  int lid = blockIdx.x;
+  const int nblocks = gridDim.x;
+  if ((nblocks & 7) == 0) lid = (lid & 7) * (nblocks >> 3) + (lid >> 3);
+  constexpr int GM = 8;
+  const int per_group = GM * tiles_n;
+  const int first_m = (lid / per_group) * GM;
+  const int gsz = min(GM, tiles_m - first_m);
+  const int tile_m = first_m + (lid % per_group) % gsz, tile_n = (lid % per_group) / gsz;
   const int mb = tile_m * BM, nb = tile_n * BN;
 
   const int st_r = tid >> 3, st_c = tid & 7;
@@ -306,12 +317,19 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const ts_bf16* __restri
 
   uint4 wr[LW], ar[LA];
   auto gload = [&](int k0) {
-    const bool ok = (k0 + st_c * 8) < K;
-    const int kk = ok ? k0 : 0;
+    if (k0 + 64 <= K) {   // full K step: plain loads, nothing consumes them at issue time
 #pragma unroll
-    for (int i = 0; i < LW; ++i) wr[i] = ldg16_or_zero(wptr[i] + kk, ok);
+      for (int i = 0; i < LW; ++i) wr[i] = ldg16(wptr[i] + k0);
 #pragma unroll
-    for (int i = 0; i < LA; ++i) ar[i] = ldg16_or_zero(aptr[i] + kk, ok);
+      for (int i = 0; i < LA; ++i) ar[i] = ldg16(aptr[i] + k0);
+    } else {
+      const bool ok = (k0 + st_c * 8) < K;
+      const int kk = ok ? k0 : 0;
+#pragma unroll
+      for (int i = 0; i < LW; ++i) wr[i] = ldg16_or_zero(wptr[i] + kk, ok);
+#pragma unroll
+      for (int i = 0; i < LA; ++i) ar[i] = ldg16_or_zero(aptr[i] + kk, ok);
+    }
   };
   auto sstore = [&](int buf) {
 #pragma unroll
@@ -449,6 +467,25 @@ void launch_skinny(const SkinnyArgs& a, int mrows, int NT, dim3 grid, hipStream_
 
 }  // namespace
 
+template <int BM, int BN>
+int launch_tiled(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, void* C, bool f32out, int M, int N, int K,
+                 hipStream_t s) {
+  const int tiles_m = cdiv(M, BM), tiles_n = cdiv(N, BN);
+  const size_t smem = (size_t)2 * (BM + BN) * 9 * sizeof(uint4);
+  dim3 grid(tiles_m * tiles_n);
+  if (f32out) {
+    allow_lds(gemm_tiled_kernel<BM, BN, true>, smem);
+    TS_LAUNCH("gemm_tiled", (gemm_tiled_kernel<BM, BN, true>), grid, dim3(256), smem, s, A, W, residual, C, M, N, K,
+              tiles_m, tiles_n);
+  } else {
+    allow_lds(gemm_tiled_kernel<BM, BN, false>, smem);
+    TS_LAUNCH("gemm_tiled", (gemm_tiled_kernel<BM, BN, false>), grid, dim3(256), smem, s, A, W, residual, C, M, N, K,
+              tiles_m, tiles_n);
+  }
+  TS_LAUNCH_CHECK("gemm_tiled");
+  return TS_OK;
+}
+
 size_t gemm_workspace_bytes(int M, int N, int K) {
   if (M <= 0 || N <= 0 || K <= 0 || M > kSkinnyMaxM) return 0;
   SkinnyPlan p = plan_skinny(N, K);
@@ -478,19 +515,11 @@ int launch_gemm(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, voi
     }
     return TS_OK;
   }
-  constexpr int BM = 128, BN = 128;
-  const int tiles_m = cdiv(M, BM), tiles_n = cdiv(N, BN);
-  const size_t smem = (size_t)2 * (BM + BN) * 9 * sizeof(uint4);
-  dim3 grid(tiles_m * tiles_n);
-  if (f32out) {
-    allow_lds(gemm_tiled_kernel<BM, BN, true>, smem);
-    TS_LAUNCH("gemm_tiled", (gemm_tiled_kernel<BM, BN, true>), grid, dim3(256), smem, s, A, W, residual, C, M, N, K, tiles_m);
-  } else {
-    allow_lds(gemm_tiled_kernel<BM, BN, false>, smem);
-    TS_LAUNCH("gemm_tiled", (gemm_tiled_kernel<BM, BN, false>), grid, dim3(256), smem, s, A, W, residual, C, M, N, K, tiles_m);
-  }
-  TS_LAUNCH_CHECK("gemm_tiled");
-  return TS_OK;
+  // 256 x 256 tiles (each wave 128 x 128: 64 flop per LDS byte) when they still give every
+  // CU work; 128 x 128 tiles otherwise.
+  if ((long)cdiv(M, 256) * cdiv(N, 256) >= 192)
+    return launch_tiled<256, 256>(A, W, residual, C, f32out, M, N, K, s);
+  return launch_tiled<128, 128>(A, W, residual, C, f32out, M, N, K, s);
 }
 
 int launch_moe_gemm(const ts_bf16* A, const int32_t* row_map, int row_div, const ts_bf16* W, const int32_t* offsets,
