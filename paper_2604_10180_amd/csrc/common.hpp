@@ -104,6 +104,9 @@ int launch_copy16(const void* src, void* dst, size_t bytes, hipStream_t s);
 size_t gemm_workspace_bytes(int M, int N, int K);
 int launch_gemm(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, void* C, bool f32out, int M, int N,
                 int K, void* ws, size_t ws_bytes, hipStream_t s);
+bool gemm_mfma256_supported(int M, int N, int K);
+int launch_gemm_mfma256(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, ts_bf16* C, int M, int N, int K,
+                        hipStream_t s);
 int launch_moe_gemm(const ts_bf16* A, const int32_t* row_map, int row_div, const ts_bf16* W,
                     const int32_t* offsets, ts_bf16* C, int rows, int E, int N, int K, hipStream_t s);
 

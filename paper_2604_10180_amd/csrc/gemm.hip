@@ -515,10 +515,13 @@ int launch_gemm(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, voi
     }
     return TS_OK;
   }
-  // 256 x 256 tiles (each wave 128 x 128: 64 flop per LDS byte) when they still give every
-  // CU work; 128 x 128 tiles otherwise.
-  if ((long)cdiv(M, 256) * cdiv(N, 256) >= 192)
+  // 256 x 256 tiles when they still give every CU work (direct-to-LDS kernel when the shape
+  // allows it), 128 x 128 tiles otherwise.
+  if ((long)cdiv(M, 256) * cdiv(N, 256) >= 192) {
+    if (!f32out && gemm_mfma256_supported(M, N, K))
+      return launch_gemm_mfma256(A, W, residual, reinterpret_cast<ts_bf16*>(C), M, N, K, s);
     return launch_tiled<256, 256>(A, W, residual, C, f32out, M, N, K, s);
+  }
   return launch_tiled<128, 128>(A, W, residual, C, f32out, M, N, K, s);
 }
 
