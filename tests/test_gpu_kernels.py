@@ -207,6 +207,10 @@ def test_attention_decode_degenerate(B):
     (4, 2, 64, [1, 63, 64, 65, 200], True),
     (8, 2, 128, [130, 31, 257], True),
     (4, 4, 128, [100, 70], False),
+    (16, 2, 128, [300, 129], True),      # GQA group 8: eight heads per workgroup, 32-query blocks
+    (6, 2, 64, [97, 260], True),         # group 3: one head per workgroup, 256-query blocks
+    (8, 8, 64, [513], False),            # no GQA, non-causal, ragged tail block
+    (32, 8, 128, [1000, 24], True),      # the 8B head layout over several query and key blocks
 ])
 def test_attention_prefill(B, nq, nkv, d, seqs, causal):
     g = gen(sum(seqs) + d)
