@@ -2,10 +2,12 @@
 // Sec. 2.3), flash-style: keys are visited in blocks of 64 with an online softmax, nothing of
 // size L x L is materialised.
 //
-// Workgroup = 8 waves (two per SIMD: one wave's softmax arithmetic overlaps the other's
-// MFMAs) = one kv head x the query heads that share it x consecutive 32-query blocks.  With
-// the usual group of 4 query heads that is 4 heads x 64 queries, so a staged K/V block is used
-// by 256 query rows and all waves of a query block stop at the same causal boundary.
+// Workgroup = 4 waves (one per SIMD) = one kv head x the query heads that share it x
+// consecutive 32-query blocks; two workgroups fit a CU, so each SIMD holds two waves of
+// unrelated workgroups that drift apart and fill each other's softmax and barrier gaps (an
+// 8-wave workgroup with a three-stage ring, still selectable through the NW template
+// parameter, measured the same speed).  With the usual group of 4 query heads a workgroup is
+// 4 heads x 32 queries, so all its waves stop at the same causal boundary.
 //
 // Orientation (32x32x16 bf16 MFMA throughout):
 //   S^T[key, query] = K . Q^T      A = K rows from LDS, B = Q fragments held in registers
@@ -35,46 +37,55 @@ constexpr int kKeysPerBlock = 64;
 constexpr int kStageU4 = 2 * kKeysPerBlock * 16;          // K tile + V tile at d = 128: 32 KiB
 constexpr int kImgRowPad = 8;                             // bytes of padding per output-image row
 constexpr int kImgU4PerWave = 32 * (256 + kImgRowPad) / 16;
+static_assert(3 * kImgU4PerWave <= kStageU4, "three per-wave output images must fit one ring stage");
 
 // Separate LDS variables per ring stage: direct loads into one provably do not alias operand
 // reads from the other, so those reads are not made to wait for the loads in flight.
 __shared__ uint4 g_kv0[kStageU4];
 __shared__ uint4 g_kv1[kStageU4];
-__shared__ uint4 g_oimg[8 * kImgU4PerWave];
+__shared__ uint4 g_kv2[kStageU4];
 
-__device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0) only
+// s_waitcnt on the vector-memory counter only (N <= 15): at most N loads of this wave still in flight
+template <int N> __device__ __forceinline__ void wait_vm() { __builtin_amdgcn_s_waitcnt(0x0F70 | N); }
 
 // chunk swizzles (row = key index inside the block)
 template <int D> __device__ __forceinline__ int kswz(int row) { return D == 128 ? (row & 15) : ((row >> 1) & 7); }
 template <int D> __device__ __forceinline__ int vswz(int row) { return D == 128 ? 4 * (row & 3) : 4 * ((row >> 1) & 1); }
 
-template <int D>
+template <int D, int NW>
 __device__ __forceinline__ void attn_prefill_body(const ts_bf16* __restrict__ q, const ts_bf16* __restrict__ k,
                                                   const ts_bf16* __restrict__ v, int q_stride, int kv_stride,
                                                   const int32_t* __restrict__ cu, ts_bf16* __restrict__ out, int nq,
-                                                  int nkv, int hpw, float c_scale, int causal) {
+                                                  int nkv, int hpw, int nseq, int nqb, float c_scale,
+                                                  int causal) {
   constexpr int KB = kKeysPerBlock;
   constexpr int STEPS = D / 16;        // 16-wide d steps of the QK product
   constexpr int DT = D / 32;           // 32-wide output column tiles
   constexpr int CPR = D / 8;           // 16-byte chunks per row
   constexpr int ROWB = D * 2;          // bytes per row
   constexpr int RPI = 1024 / ROWB;     // rows per direct-load instruction
-  constexpr int LPW = KB / RPI / 8;    // direct loads per wave per tile
+  constexpr int LPW = KB / RPI / NW;   // direct loads per wave per tile
   constexpr int VT = KB * ROWB;        // byte offset of the V tile inside a stage
   constexpr int IMGROW = ROWB + kImgRowPad;
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r32 = lane & 31, g = lane >> 5;
   const int group = nq / nkv;
-  const int qsubs = 8 / hpw;                      // 32-query blocks per workgroup
+  const int qsubs = NW / hpw;                      // 32-query blocks per workgroup
   const int QB = 32 * qsubs;
   const int head_local = wave % hpw, qsub = wave / hpw;
   const int hgroups = group / hpw;
-  const int kvh = blockIdx.y / hgroups, hg = blockIdx.y % hgroups;
+  // Workgroup id -> (head group, sequence) fastest, query block slowest and descending: the long
+  // (late) query blocks are scheduled first, and because consecutive ids go round-robin to the
+  // 8 XCDs every XCD gets the same mix of block lengths while one (kv head, sequence) keeps
+  // landing on the same XCD, whose L2 then serves its K/V to all query blocks.
+  const int npairs = nkv * hgroups * nseq;
+  const int pair = blockIdx.x % npairs;
+  const int qb = nqb - 1 - blockIdx.x / npairs;
+  const int sq = pair / (nkv * hgroups), hy = pair % (nkv * hgroups);
+  const int kvh = hy / hgroups, hg = hy % hgroups;
   const int h = kvh * group + hg * hpw + head_local;
-  const int sq = blockIdx.z;
   const int a = cu[sq], n = cu[sq + 1] - a;
-  const int qb = gridDim.x - 1 - blockIdx.x;       // long (late) query blocks are scheduled first
   if (qb * QB >= n) return;
   const int q0 = qb * QB + qsub * 32;             // first query of this wave
   const int qi = q0 + r32;                        // this lane's query
@@ -93,20 +104,34 @@ __device__ __forceinline__ void attn_prefill_body(const ts_bf16* __restrict__ q,
   const ts_bf16* kbase = k + (size_t)a * kv_stride + (size_t)kvh * D;
   const ts_bf16* vbase = v + (size_t)a * kv_stride + (size_t)kvh * D;
   int ld_row[LPW], ld_kc[LPW], ld_vc[LPW];
+  uint32_t ld_koff[LPW], ld_voff[LPW];      // byte offsets from the first key of a block (full blocks)
 #pragma unroll
   for (int i = 0; i < LPW; ++i) {
-    const int row = (i * 8 + wave) * RPI + lane / CPR, p = lane % CPR;
+    const int row = (i * NW + wave) * RPI + lane / CPR, p = lane % CPR;
     ld_row[i] = row;
     ld_kc[i] = (p ^ kswz<D>(row)) * 8;
     ld_vc[i] = (p ^ vswz<D>(row)) * 8;
+    ld_koff[i] = ((uint32_t)row * (uint32_t)kv_stride + ld_kc[i]) * 2u;
+    ld_voff[i] = ((uint32_t)row * (uint32_t)kv_stride + ld_vc[i]) * 2u;
   }
   auto issue = [&](uint4* stage, int kb) {
+    if (kb * KB + KB <= n) {   // full block: uniform base + per-lane constant offset, no address arithmetic
+      const char* kb_base = reinterpret_cast<const char*>(kbase) + (size_t)kb * KB * kv_stride * 2;
+      const char* vb_base = reinterpret_cast<const char*>(vbase) + (size_t)kb * KB * kv_stride * 2;
 #pragma unroll
-    for (int i = 0; i < LPW; ++i) {
-      const size_t key = (size_t)min(kb * KB + ld_row[i], n - 1);
-      uint4* dst = stage + (i * 8 + wave) * 64;
-      __builtin_amdgcn_global_load_lds(kbase + key * kv_stride + ld_kc[i], (lds_void*)dst, 16, 0, 0);
-      __builtin_amdgcn_global_load_lds(vbase + key * kv_stride + ld_vc[i], (lds_void*)(dst + VT / 16), 16, 0, 0);
+      for (int i = 0; i < LPW; ++i) {
+        uint4* dst = stage + (i * NW + wave) * 64;
+        __builtin_amdgcn_global_load_lds(kb_base + ld_koff[i], (lds_void*)dst, 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(vb_base + ld_voff[i], (lds_void*)(dst + VT / 16), 16, 0, 0);
+      }
+    } else {                   // last, partial block: rows past the end re-read the last key (masked later)
+#pragma unroll
+      for (int i = 0; i < LPW; ++i) {
+        const size_t key = (size_t)min(kb * KB + ld_row[i], n - 1);
+        uint4* dst = stage + (i * NW + wave) * 64;
+        __builtin_amdgcn_global_load_lds(kbase + key * kv_stride + ld_kc[i], (lds_void*)dst, 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(vbase + key * kv_stride + ld_vc[i], (lds_void*)(dst + VT / 16), 16, 0, 0);
+      }
     }
   };
 
@@ -141,15 +166,24 @@ __device__ __forceinline__ void attn_prefill_body(const ts_bf16* __restrict__ q,
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int e = 0; e < 16; ++e) s[t][e] = 0.f;
+    // K fragments run three d-steps ahead of the MFMAs that consume them
+    U4 kf[STEPS][2];
+    auto load_k = [&](int sp) {
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
+        kf[sp][t].u = *reinterpret_cast<const uint4*>(st + t * 32 * ROWB + krow + (((sp * 2 + g) ^ kx) * 16));
+    };
+    load_k(0);
+    load_k(1);
+    load_k(2);
 #pragma unroll
     for (int sp = 0; sp < STEPS; ++sp) {
+      __builtin_amdgcn_sched_barrier(0);
+      if (sp + 3 < STEPS) load_k(sp + 3);
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
-        U4 kf;
-        kf.u = *reinterpret_cast<const uint4*>(st + t * 32 * ROWB + krow + (((sp * 2 + g) ^ kx) * 16));
-        s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf.b, qf[sp].b, s[t], 0, 0, 0);
-      }
+      for (int t = 0; t < 2; ++t) s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[sp][t].b, qf[sp].b, s[t], 0, 0, 0);
     }
+    __builtin_amdgcn_sched_barrier(0);
     // ---- masking: only blocks that reach the causal diagonal or the end of the sequence
     const int key0 = kb * KB + g * 4;                  // key of (t, e): key0 + t*32 + (e/4)*8 + e%4
     const bool need_mask = (kb * KB + KB > n) || (causal && kb * KB + KB - 1 > q0);
@@ -161,15 +195,26 @@ __device__ __forceinline__ void attn_prefill_body(const ts_bf16* __restrict__ q,
         for (int e = 0; e < 16; ++e)
           if (key0 + t * 32 + (e >> 2) * 8 + (e & 3) > lim) s[t][e] = -INFINITY;
     }
-    // ---- online softmax (scores stay raw; c_scale = scale * log2(e) enters the exponent)
+    // ---- online softmax.  Scores stay raw; c_scale = scale * log2(e) enters the exponent.
+    // The reference maximum m_run is moved only when some score of the block would exceed it by
+    // more than 8 binades (p <= 256 keeps bf16's relative precision and is far from fp32
+    // overflow in the row sum); o / l does not depend on which reference is used, and the 64
+    // accumulator rescales are then skipped for almost every block.
     float bm = s[0][0];
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int e = 0; e < 16; ++e) bm = fmaxf(bm, s[t][e]);
-    bm = fmaxf(bm, __shfl_xor(bm, 32, 64));
-    const float m_new = fmaxf(m_run, bm);              // finite from the first block on (key 0 is visible)
-    const float mc = m_new * c_scale;
+    bm = fmaxf(bm, __shfl_xor(bm, 32, 64));            // finite from the first block on (key 0 is visible)
+    if (__builtin_amdgcn_ballot_w64((bm - m_run) * c_scale > 8.0f) != 0) {
+      const float m_new = fmaxf(m_run, bm);
+      const float alpha = __builtin_amdgcn_exp2f((m_run - m_new) * c_scale);   // first block: exp2(-inf) = 0
+      l_run *= alpha;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
+      m_run = m_new;
+    }
+    const float mc = m_run * c_scale;
     float ps = 0.f;
     U4 pf[2][2];
 #pragma unroll
@@ -183,13 +228,6 @@ __device__ __forceinline__ void attn_prefill_body(const ts_bf16* __restrict__ q,
           ps += p0 + p1;
           pf[t][c].w[w2] = pack_bf16(p0, p1);
         }
-    if (__builtin_amdgcn_ballot_w64(m_new > m_run) != 0) {   // rescale only when some lane's max moved
-      const float alpha = __builtin_amdgcn_exp2f(m_run * c_scale - mc);   // first block: exp2(-inf) = 0
-      l_run *= alpha;
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
-      m_run = m_new;
-    }
     l_run += ps;
     // ---- O^T += V^T . P^T : for product (t, c) the lane's k-slots are the keys of its
     // accumulator elements 8c .. 8c+7 of tile t: rows t*32 + 16c + 4g + {0..3} and + 8
@@ -206,30 +244,54 @@ __device__ __forceinline__ void attn_prefill_body(const ts_bf16* __restrict__ q,
           o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vt.b, pf[t][c].b, o[dt], 0, 0, 0);
         }
   };
-  // one ring step: prefetch the next block (the last step re-fetches the final block into the
-  // idle stage rather than branching), compute, then make the prefetched stage visible
-  auto step = [&](const uint4* cur, uint4* nxt, int kb) {
-    issue(nxt, min(kb + 1, nkb - 1));
+  // One ring step.  Eight waves use three stages: prefetch block kb+2 into the stage that was
+  // read in step kb-1 (past the end the final block is fetched again into an idle stage rather
+  // than branching), compute block kb, then wait until block kb+1 has landed: only the loads
+  // issued in this step may still be in flight.  Four waves (two workgroups per CU, half the
+  // LDS each) use two stages and wait for everything.
+  constexpr int AHEAD = (NW == 8) ? 2 : 1;
+  auto step = [&](const uint4* cur, uint4* tgt, int kb) {
+    issue(tgt, min(kb + AHEAD, nkb - 1));
     __builtin_amdgcn_sched_barrier(0);
     if (!(causal && kb * KB > q0 + 31)) block(cur, kb);   // keys entirely above this wave's diagonal: skip
-    wait_vm0();
+    wait_vm<(AHEAD - 1) * 2 * LPW>();
     __syncthreads();
   };
 
-  issue(g_kv0, 0);
-  wait_vm0();
-  __syncthreads();
   int kb = 0;
-  for (; kb + 2 <= nkb; kb += 2) {
-    step(g_kv0, g_kv1, kb);
-    step(g_kv1, g_kv0, kb + 1);
+  if constexpr (NW == 8) {
+    issue(g_kv0, 0);
+    issue(g_kv1, min(1, nkb - 1));
+    wait_vm<2 * LPW>();
+    __syncthreads();
+    for (; kb + 3 <= nkb; kb += 3) {
+      step(g_kv0, g_kv2, kb);
+      step(g_kv1, g_kv0, kb + 1);
+      step(g_kv2, g_kv1, kb + 2);
+    }
+    if (kb < nkb) {
+      step(g_kv0, g_kv2, kb);
+      if (kb + 1 < nkb) step(g_kv1, g_kv0, kb + 1);
+    }
+  } else {
+    issue(g_kv0, 0);
+    wait_vm<0>();
+    __syncthreads();
+    for (; kb + 2 <= nkb; kb += 2) {
+      step(g_kv0, g_kv1, kb);
+      step(g_kv1, g_kv0, kb + 1);
+    }
+    if (kb < nkb) step(g_kv0, g_kv1, kb);
   }
-  if (kb < nkb) step(g_kv0, g_kv1, kb);
+  wait_vm<0>();        // the trailing re-fetches have landed,
+  __syncthreads();     // and every wave is done with the ring: it now holds the output images
 
   // ---- epilogue: normalise, round, transpose through this wave's LDS image, store whole rows
   l_run += __shfl_xor(l_run, 32, 64);
   const float inv = 1.0f / l_run;
-  char* img = reinterpret_cast<char*>(g_oimg + wave * kImgU4PerWave);
+  uint4* img_stage = wave < 3 ? g_kv0 : g_kv1;
+  if constexpr (NW == 8) img_stage = wave < 3 ? g_kv0 : (wave < 6 ? g_kv1 : g_kv2);
+  char* img = reinterpret_cast<char*>(img_stage + (wave % 3) * kImgU4PerWave);
 #pragma unroll
   for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -253,37 +315,34 @@ __device__ __forceinline__ void attn_prefill_body(const ts_bf16* __restrict__ q,
 }  // namespace
 
 // (plain kernels around the templated body: the ring stages are namespace-scope LDS variables)
-__global__ __launch_bounds__(512) void attn_prefill_d128_kernel(const ts_bf16* q, const ts_bf16* k, const ts_bf16* v,
-                                                                int q_stride, int kv_stride, const int32_t* cu,
-                                                                ts_bf16* out, int nq, int nkv, int hpw, float c_scale,
-                                                                int causal) {
-  attn_prefill_body<128>(q, k, v, q_stride, kv_stride, cu, out, nq, nkv, hpw, c_scale, causal);
+#define TS_PREFILL_ARGS const ts_bf16* q, const ts_bf16* k, const ts_bf16* v, int q_stride, int kv_stride, \
+                        const int32_t* cu, ts_bf16* out, int nq, int nkv, int hpw, int nseq, int nqb, float c_scale, int causal
+#define TS_PREFILL_PASS q, k, v, q_stride, kv_stride, cu, out, nq, nkv, hpw, nseq, nqb, c_scale, causal
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_prefill_d128_w4_kernel(TS_PREFILL_ARGS) {
+  attn_prefill_body<128, 4>(TS_PREFILL_PASS);
 }
-__global__ __launch_bounds__(512) void attn_prefill_d64_kernel(const ts_bf16* q, const ts_bf16* k, const ts_bf16* v,
-                                                               int q_stride, int kv_stride, const int32_t* cu,
-                                                               ts_bf16* out, int nq, int nkv, int hpw, float c_scale,
-                                                               int causal) {
-  attn_prefill_body<64>(q, k, v, q_stride, kv_stride, cu, out, nq, nkv, hpw, c_scale, causal);
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void attn_prefill_d64_w4_kernel(TS_PREFILL_ARGS) {
+  attn_prefill_body<64, 4>(TS_PREFILL_PASS);
 }
+
 
 int launch_attention_prefill(const ts_bf16* q, const ts_bf16* k, const ts_bf16* v, int q_stride, int kv_stride,
                              const int32_t* cu, ts_bf16* out, int S, int T, int max_seqlen, int nq, int nkv, int d,
                              float scale, int causal, hipStream_t s) {
   if (S == 0 || T == 0 || max_seqlen == 0) return TS_OK;
   const float c_scale = scale * 1.4426950408889634f;
-  // query heads per workgroup: the largest power of two (<= 8) that divides the GQA group
+  // query heads per workgroup: the largest power of two (<= waves) that divides the GQA group
+  constexpr int NW = 4;
   const int group = nq / nkv;
   int hpw = 1;
-  while (hpw < 8 && group % (hpw * 2) == 0) hpw *= 2;
-  const int QB = 32 * (8 / hpw);
-  dim3 grid(cdiv(max_seqlen, QB), nkv * (group / hpw), S);
-  if (d == 128) {
-    TS_LAUNCH("attn_prefill", attn_prefill_d128_kernel, grid, dim3(512), 0, s, q, k, v, q_stride, kv_stride, cu, out, nq,
-              nkv, hpw, c_scale, causal);
-  } else {
-    TS_LAUNCH("attn_prefill", attn_prefill_d64_kernel, grid, dim3(512), 0, s, q, k, v, q_stride, kv_stride, cu, out, nq,
-              nkv, hpw, c_scale, causal);
-  }
+  while (hpw < NW && group % (hpw * 2) == 0) hpw *= 2;
+  const int QB = 32 * (NW / hpw);
+  const int nqb = cdiv(max_seqlen, QB);
+  dim3 grid(nqb * nkv * (group / hpw) * S);
+#define TS_PREFILL_LAUNCH(kern, threads) \
+  TS_LAUNCH("attn_prefill", kern, grid, dim3(threads), 0, s, q, k, v, q_stride, kv_stride, cu, out, nq, nkv, hpw, S, nqb, c_scale, causal)
+  if (d == 128) TS_PREFILL_LAUNCH(attn_prefill_d128_w4_kernel, 256);
+  else TS_PREFILL_LAUNCH(attn_prefill_d64_w4_kernel, 256);
   TS_LAUNCH_CHECK("attn_prefill");
   return TS_OK;
 }
