@@ -35,9 +35,10 @@ struct SkinnyArgs {
 // staged in LDS and shared by the 4 waves.  K advances 128 per iteration; lane (r, g) of a
 // wave (r = lane%16, g = lane/16) holds for MFMA step j the 8 k-values of 16-byte chunk
 // j*4+g, so a row's four lanes read 64 contiguous bytes per load.
-template <int MT, int NT, bool GROUPED>
+template <int MT, int NT, bool GROUPED, int NS>
 __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs a) {
   constexpr int ROWS = MT * 16;
+  constexpr int D = NS - 1;    // prefetch distance in 128-wide K slabs
   constexpr int LDS_ROW = 17;  // uint4 per staged row: 16 data + 1 pad (272 B stride, conflict-free b128 reads)
   extern __shared__ uint4 smem[];
   uint4(*lds)[ROWS][LDS_ROW] = reinterpret_cast<uint4(*)[ROWS][LDS_ROW]>(smem);
@@ -82,11 +83,11 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs a) {
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // Three-stage ring, prefetch distance 2: while slab `it` is multiplied, the W fragments
-    // of slabs it+1 and it+2 are in flight in registers and the activation slab it+1 moves
+    // NS-stage ring, prefetch distance D = NS-1: while slab `it` is multiplied, the W fragments
+    // of slabs it+1 .. it+D are in flight in registers and the activation slab it+D-1 moves
     // from registers to LDS.  One barrier per slab; barriers wait on LDS only, never on the
     // outstanding global loads.
-    U4 wbuf[3][NT][4], areg[MT];
+    U4 wbuf[NS][NT][4], areg[MT];
 
     // Rows past the end of A or W are clamped to a valid row: they only feed output elements
     // that are never stored.  Only a K tail (K % 128 != 0) needs zeros, and zeroing the W
@@ -144,38 +145,41 @@ __global__ __launch_bounds__(256) void gemm_skinny_kernel(SkinnyArgs a) {
       auto step = [&](auto checked, auto stage, int it) {
         constexpr bool CHECKED = decltype(checked)::value;
         constexpr int u = decltype(stage)::value;
-        if (!CHECKED || it + 1 < nfull) store_a((u + 1) % 3);
-        if (!CHECKED || it + 2 < nfull) {
-          const int kn = slab(it + 2);
+        if (!CHECKED || it + D - 1 < nfull) store_a((u + D - 1) % NS);
+        if (!CHECKED || it + D < nfull) {
+          const int kn = slab(it + D);
           load_a(kn);
-          load_w(kn, wbuf[(u + 2) % 3]);
+          load_w(kn, wbuf[(u + D) % NS]);
         }
         compute(u, wbuf[u]);
         __syncthreads();
       };
       using T_ = std::true_type;
       using F_ = std::false_type;
-      using S0 = std::integral_constant<int, 0>;
-      using S1 = std::integral_constant<int, 1>;
-      using S2 = std::integral_constant<int, 2>;
-      load_a(slab(0));
-      load_w(slab(0), wbuf[0]);
-      store_a(0);
-      if (nfull > 1) {
-        load_a(slab(1));
-        load_w(slab(1), wbuf[1]);
+      // prologue: slabs 0 .. D-2 go all the way into LDS, slab D-1 stays in registers
+#pragma unroll
+      for (int p = 0; p < D; ++p) {
+        if (p < nfull) {
+          load_a(slab(p));
+          load_w(slab(p), wbuf[p]);
+          if (p < D - 1) store_a(p);
+        }
       }
       __syncthreads();
       int it = 0;
-      for (; it + 4 < nfull; it += 3) {
-        step(F_{}, S0{}, it);
-        step(F_{}, S1{}, it + 1);
-        step(F_{}, S2{}, it + 2);
+      for (; it + 2 * NS - 2 < nfull; it += NS) {
+        step(F_{}, std::integral_constant<int, 0>{}, it);
+        step(F_{}, std::integral_constant<int, 1>{}, it + 1);
+        step(F_{}, std::integral_constant<int, 2>{}, it + 2);
+        if constexpr (NS > 3) step(F_{}, std::integral_constant<int, 3>{}, it + 3);
       }
-      for (; it < nfull; it += 3) {
-        step(T_{}, S0{}, it);
-        if (it + 1 < nfull) step(T_{}, S1{}, it + 1);
-        if (it + 2 < nfull) step(T_{}, S2{}, it + 2);
+      for (; it < nfull; it += NS) {
+        step(T_{}, std::integral_constant<int, 0>{}, it);
+        if (it + 1 < nfull) step(T_{}, std::integral_constant<int, 1>{}, it + 1);
+        if (it + 2 < nfull) step(T_{}, std::integral_constant<int, 2>{}, it + 2);
+        if constexpr (NS > 3) {
+          if (it + 3 < nfull) step(T_{}, std::integral_constant<int, 3>{}, it + 3);
+        }
       }
     }
     if (kbeg + nfull * 128 < kend) {   // K tail: one partial slab, not pipelined
@@ -445,15 +449,21 @@ void allow_lds(KernelT kernel, size_t bytes) {
                               (int)bytes);
 }
 
+// Ring depth: four stages (three slabs of W in flight per wave) wherever the registers allow it.
+template <int MT, int NT> constexpr int skinny_stages() { return (MT * NT <= 8) ? 4 : 3; }
+
 template <int MT, bool GROUPED>
 void launch_skinny_mt(const SkinnyArgs& a, int NT, dim3 grid, hipStream_t s) {
-  const size_t smem = (size_t)3 * MT * 16 * 17 * sizeof(uint4);
   if (NT == 2) {
-    allow_lds(gemm_skinny_kernel<MT, 2, GROUPED>, smem);
-    TS_LAUNCH("gemm_skinny", (gemm_skinny_kernel<MT, 2, GROUPED>), grid, dim3(256), smem, s, a);
+    constexpr int NS = skinny_stages<MT, 2>();
+    const size_t smem = (size_t)NS * MT * 16 * 17 * sizeof(uint4);
+    allow_lds(gemm_skinny_kernel<MT, 2, GROUPED, NS>, smem);
+    TS_LAUNCH("gemm_skinny", (gemm_skinny_kernel<MT, 2, GROUPED, NS>), grid, dim3(256), smem, s, a);
   } else {
-    allow_lds(gemm_skinny_kernel<MT, 1, GROUPED>, smem);
-    TS_LAUNCH("gemm_skinny", (gemm_skinny_kernel<MT, 1, GROUPED>), grid, dim3(256), smem, s, a);
+    constexpr int NS = skinny_stages<MT, 1>();
+    const size_t smem = (size_t)NS * MT * 16 * 17 * sizeof(uint4);
+    allow_lds(gemm_skinny_kernel<MT, 1, GROUPED, NS>, smem);
+    TS_LAUNCH("gemm_skinny", (gemm_skinny_kernel<MT, 1, GROUPED, NS>), grid, dim3(256), smem, s, a);
   }
 }
 
