@@ -415,16 +415,25 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const ts_bf16* __restri
 namespace {
 
 constexpr int kSkinnyMaxM = 128;
+// A handful of output columns (the MoE router): the weight matrix is a few rows, so the
+// streaming kernel (looping over row blocks of A) beats one tile of the MFMA-bound kernel.
+constexpr int kSkinnyMaxN = 16;
+inline bool use_skinny(int M, int N) { return M <= kSkinnyMaxM || N <= kSkinnyMaxN; }
 
 struct SkinnyPlan {
   int NT, S, kslice;
 };
 
-SkinnyPlan plan_skinny(int N, int K) {
+// Launch shape of the streaming kernel.  128-row workgroups halve the activation re-reads,
+// but only pay when there are at least as many of them as CUs (a CU keeps a bounded number of
+// cache misses in flight, so an idle CU is lost bandwidth); otherwise 64-row workgroups, split
+// along K until there are about two per CU.
+SkinnyPlan plan_skinny(int M, int N, int K) {
   SkinnyPlan p;
   const int t2 = cdiv(N, 128), t1 = cdiv(N, 64);
   p.S = 1;
-  if (t2 >= 192) {   // enough 128-row workgroups: halves the activation re-reads from L2
+  (void)M;
+  if (t2 >= 256) {
     p.NT = 2;
   } else {
     p.NT = 1;
@@ -449,8 +458,9 @@ void allow_lds(KernelT kernel, size_t bytes) {
                               (int)bytes);
 }
 
-// Ring depth: four stages (three slabs of W in flight per wave) wherever the registers allow it.
-template <int MT, int NT> constexpr int skinny_stages() { return (MT * NT <= 8) ? 4 : 3; }
+// Ring depth: four stages (three slabs of W in flight per wave) for up to 32 token rows, where
+// it measured faster; three stages otherwise (the fourth costs occupancy at 64 rows).
+template <int MT, int NT> constexpr int skinny_stages() { return (MT <= 2 && NT == 1) ? 4 : 3; }
 
 template <int MT, bool GROUPED>
 void launch_skinny_mt(const SkinnyArgs& a, int NT, dim3 grid, hipStream_t s) {
@@ -497,16 +507,16 @@ int launch_tiled(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, vo
 }
 
 size_t gemm_workspace_bytes(int M, int N, int K) {
-  if (M <= 0 || N <= 0 || K <= 0 || M > kSkinnyMaxM) return 0;
-  SkinnyPlan p = plan_skinny(N, K);
+  if (M <= 0 || N <= 0 || K <= 0 || !use_skinny(M, N)) return 0;
+  SkinnyPlan p = plan_skinny(M, N, K);
   return p.S > 1 ? (size_t)p.S * M * N * sizeof(float) : 0;
 }
 
 int launch_gemm(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, void* C, bool f32out, int M, int N, int K,
                 void* ws, size_t ws_bytes, hipStream_t s) {
   if (M == 0) return TS_OK;
-  if (M <= kSkinnyMaxM) {
-    SkinnyPlan p = plan_skinny(N, K);
+  if (use_skinny(M, N)) {
+    SkinnyPlan p = plan_skinny(M, N, K);
     const size_t need = p.S > 1 ? (size_t)p.S * M * N * sizeof(float) : 0;
     TS_REQUIRE(need == 0 || (ws != nullptr && ws_bytes >= need), TS_ERR_WORKSPACE,
                "ts_gemm_bf16: workspace %zu bytes < required %zu", ws_bytes, need);
