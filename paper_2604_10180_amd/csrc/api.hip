@@ -61,6 +61,8 @@ struct LayerPlan {
   size_t h1, qkv, attn, x2, h2, gate_up, act, y;         // boundary buffers (byte offsets)
   size_t logits, topk_idx, topk_w, counts, offsets, perm, inv;  // MoE routing buffers
   size_t scratch, scratch_bytes;
+  size_t counters;                                       // int32 arrival counters (zeroed by the first kernel)
+  int counter_words;
   size_t total;
   size_t bytes[TS_NB_MOE];                               // size of each boundary
 };
@@ -133,6 +135,12 @@ LayerPlan plan_layer(const ts_layer_desc& d, int T, int B) {
   if (d.mode == TS_MODE_DECODE) mx(attention_decode_workspace_bytes(B, d.nq, d.nkv, d.d, d.Lcap));
   p.scratch_bytes = sc;
   p.scratch = take(sc);
+  // arrival counters of the in-kernel chunk merge of decode attention (one per sequence and kv
+  // head); the kernel leaves its words zeroed
+  int cw = 0;
+  if (d.mode == TS_MODE_DECODE) cw = B * d.nkv;
+  p.counter_words = cw;
+  p.counters = take((size_t)cw * 4);
   p.total = off;
   return p;
 }
@@ -188,10 +196,11 @@ int layer_forward_impl(const ts_layer_desc& d, const ts_layer_weights& w, const 
   ts_bf16* gate_up = reinterpret_cast<ts_bf16*>(ws + p.gate_up);
   ts_bf16* act = reinterpret_cast<ts_bf16*>(ws + p.act);
   void* scratch = ws + p.scratch;
+  int32_t* counters = p.counter_words > 0 ? reinterpret_cast<int32_t*>(ws + p.counters) : nullptr;
   const float scale = 1.0f / sqrtf((float)d.d);
   int rc;
 #define TS_STEP(call) do { rc = (call); if (rc != TS_OK) return rc; } while (0)
-  TS_STEP(launch_rmsnorm(io.x, w.gamma1, h1, T, d.H, d.eps, s));
+  TS_STEP(launch_rmsnorm(io.x, w.gamma1, h1, T, d.H, d.eps, s, counters, p.counter_words));
   TS_STEP(hook(TS_B_H1, h1));
   TS_STEP(launch_gemm(h1, w.w_qkv, nullptr, qkv, false, T, nqkv, d.H, scratch, p.scratch_bytes, s));
   TS_STEP(launch_rope(qkv, qkv + nqd, qkv + nqd + nkd, nqkv, nqkv, io.pos, io.seq_id, w.rope_cos_sin,
@@ -200,7 +209,7 @@ int layer_forward_impl(const ts_layer_desc& d, const ts_layer_weights& w, const 
   TS_STEP(hook(TS_B_QKV, qkv));
   if (d.mode == TS_MODE_DECODE) {
     TS_STEP(launch_attention_decode(qkv, nqkv, io.kcache, io.vcache, io.seq_lens, attn, B, d.nq, d.nkv, d.d, d.Lcap,
-                                    scale, scratch, p.scratch_bytes, s));
+                                    scale, scratch, p.scratch_bytes, s, counters));
   } else {
     TS_STEP(launch_attention_prefill(qkv, qkv + nqd, qkv + nqd + nkd, nqkv, nqkv, io.cu_seqlens, attn, B, T,
                                      io.max_seqlen, d.nq, d.nkv, d.d, scale, 1, s));

@@ -35,7 +35,9 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(const ts_bf16* _
                                                                 const int32_t* __restrict__ seq_lens,
                                                                 float* __restrict__ part, int q_stride, int nq, int nkv,
                                                                 int Lcap, int NCH, int chunk_target,
-                                                                float c_scale /* scale * log2(e) */) {
+                                                                float c_scale /* scale * log2(e) */,
+                                                                int32_t* __restrict__ counters,
+                                                                ts_bf16* __restrict__ out) {
   constexpr int KSTEPS = D / 32;   // MFMA k-steps for Q.K
   constexpr int DT = D / 16;       // 16-wide output column tiles
   constexpr int CPR = D / 8;       // 16-byte chunks per cache row
@@ -52,7 +54,11 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(const ts_bf16* _
   const int l16 = lane & 15, gq = lane >> 4;
   const int g = nq / nkv;
   const int len = seq_lens[b];
-  if (len <= 0) return;
+  if (len <= 0) {   // empty sequence: zero rows
+    if (ch == 0)
+      for (int idx = tid; idx < g * D; idx += 256) out[((size_t)b * nq + (size_t)kvh * g) * D + idx] = 0;
+    return;
+  }
   const int nchunk = decode_nchunk(len, NCH, chunk_target);
   if (ch >= nchunk) return;
   // chunks are whole 32-key blocks, spread as evenly as possible (sizes differ by one block),
@@ -188,13 +194,52 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(const ts_bf16* _
       acc += f * sm_o[((size_t)w * 16 + h) * D + col];
       L += f * sm_l[w * 16 + h];
     }
+    if (nchunk == 1) {   // the only chunk of its sequence: final result (what the merge computes for one chunk)
+      out[((size_t)b * nq + (size_t)kvh * g + h) * D + col] = f_to_bf(acc / L);
+      continue;
+    }
     float* dst = part + (((size_t)b * nq + (size_t)kvh * g + h) * NCH + ch) * (D + 2);
-    dst[col] = acc;
-    if (col == 0) {
-      dst[D] = M;
-      dst[D + 1] = L;
+    if (counters != nullptr) {   // read by another workgroup of this launch: device-coherent stores
+      st_dev_f32(dst + col, acc);
+      if (col == 0) {
+        st_dev_f32(dst + D, M);
+        st_dev_f32(dst + D + 1, L);
+      }
+    } else {
+      dst[col] = acc;
+      if (col == 0) {
+        dst[D] = M;
+        dst[D + 1] = L;
+      }
     }
   }
+  if (counters == nullptr || nchunk == 1) return;
+
+  // ---- merge fused into this launch: the last chunk of this (sequence, kv head) to arrive
+  // combines all chunks in chunk order (the same arithmetic as attn_decode_merge_kernel) and
+  // re-arms the counter.  Partials travel through device-coherent stores and loads (other chunks
+  // ran on other XCDs); every wave waits for its stores before the arrival is counted.
+  __shared__ int s_last;
+  wait_stores();
+  __syncthreads();
+  if (tid == 0) s_last = (atomicAdd(&counters[b * nkv + kvh], 1) == nchunk - 1);
+  __syncthreads();
+  if (!s_last) return;
+  for (int idx = tid; idx < g * D; idx += 256) {
+    const int h = idx / D, col = idx % D;
+    const float* p = part + ((size_t)b * nq + (size_t)kvh * g + h) * NCH * (D + 2);
+    float M = -INFINITY;
+    for (int c = 0; c < nchunk; ++c) M = fmaxf(M, ld_dev_f32(p + (size_t)c * (D + 2) + D));
+    float acc = 0.f, L = 0.f;
+    for (int c = 0; c < nchunk; ++c) {
+      const float mc = ld_dev_f32(p + (size_t)c * (D + 2) + D);
+      const float f = (mc == -INFINITY) ? 0.f : exp2f(mc - M);
+      acc += f * ld_dev_f32(p + (size_t)c * (D + 2) + col);
+      L += f * ld_dev_f32(p + (size_t)c * (D + 2) + D + 1);
+    }
+    out[((size_t)b * nq + (size_t)kvh * g + h) * D + col] = f_to_bf(acc / L);
+  }
+  if (tid == 0) __hip_atomic_store(&counters[b * nkv + kvh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 template <int D>
@@ -210,6 +255,7 @@ __global__ __launch_bounds__(D) void attn_decode_merge_kernel(const float* __res
     return;
   }
   const int nchunk = decode_nchunk(len, NCH, chunk_target);
+  if (nchunk == 1) return;   // written by the split kernel itself
   const float* p = part + (size_t)bh * NCH * (D + 2);
   float M = -INFINITY;
   for (int c = 0; c < nchunk; ++c) M = fmaxf(M, p[(size_t)c * (D + 2) + D]);
@@ -252,7 +298,7 @@ size_t attention_decode_workspace_bytes(int B, int nq, int nkv, int d, int Lcap)
 
 int launch_attention_decode(const ts_bf16* q, int q_stride, const ts_bf16* kc, const ts_bf16* vc, const int32_t* seq_lens,
                             ts_bf16* out, int B, int nq, int nkv, int d, int Lcap, float scale, void* ws,
-                            size_t ws_bytes, hipStream_t s) {
+                            size_t ws_bytes, hipStream_t s, int32_t* counters) {
   if (B == 0) return TS_OK;
   const DecodePlan plan = decode_plan(B, nkv, Lcap);
   const int NCH = plan.NCH;
@@ -262,22 +308,30 @@ int launch_attention_decode(const ts_bf16* q, int q_stride, const ts_bf16* kc, c
   const float c_scale = scale * 1.4426950408889634f;
   dim3 grid((unsigned)NCH * nkv * B);
   float* part = reinterpret_cast<float*>(ws);
+  // Merge inside the split kernel (last chunk to arrive) when sequences can have many chunks: the
+  // merge kernel then costs more than the coherent partial traffic (ragged 70B shape: 426 us
+  // against 441 + 18); with one or two chunks the separate kernel is cheaper, with one chunk
+  // there is nothing to merge.
+  if (NCH < 4) counters = nullptr;
+  const bool merge_kernel = counters == nullptr && NCH > 1;
   if (d == 128) {
     const size_t stage = (size_t)4 * kBlockKeys * 17 * sizeof(uint4);
     const size_t merge = (size_t)(4 * 16 * 128 + 128) * sizeof(float);
     const size_t smem = stage > merge ? stage : merge;
     TS_LAUNCH("attn_decode_split", attn_decode_split_kernel<128>, grid, dim3(256), smem, s, q, kc, vc, seq_lens, part, q_stride, nq,
-                       nkv, Lcap, NCH, plan.chunk_target, c_scale);
+                       nkv, Lcap, NCH, plan.chunk_target, c_scale, counters, out);
     TS_LAUNCH_CHECK("attn_decode_split");
-    TS_LAUNCH("attn_decode_merge", attn_decode_merge_kernel<128>, dim3(B * nq), dim3(128), 0, s, part, seq_lens, out, nq, NCH, plan.chunk_target);
+    if (merge_kernel)
+      TS_LAUNCH("attn_decode_merge", attn_decode_merge_kernel<128>, dim3(B * nq), dim3(128), 0, s, part, seq_lens, out, nq, NCH, plan.chunk_target);
   } else {
     const size_t stage = (size_t)4 * kBlockKeys * 9 * sizeof(uint4);
     const size_t merge = (size_t)(4 * 16 * 64 + 128) * sizeof(float);
     const size_t smem = stage > merge ? stage : merge;
     TS_LAUNCH("attn_decode_split", attn_decode_split_kernel<64>, grid, dim3(256), smem, s, q, kc, vc, seq_lens, part, q_stride, nq,
-                       nkv, Lcap, NCH, plan.chunk_target, c_scale);
+                       nkv, Lcap, NCH, plan.chunk_target, c_scale, counters, out);
     TS_LAUNCH_CHECK("attn_decode_split");
-    TS_LAUNCH("attn_decode_merge", attn_decode_merge_kernel<64>, dim3(B * nq), dim3(64), 0, s, part, seq_lens, out, nq, NCH, plan.chunk_target);
+    if (merge_kernel)
+      TS_LAUNCH("attn_decode_merge", attn_decode_merge_kernel<64>, dim3(B * nq), dim3(64), 0, s, part, seq_lens, out, nq, NCH, plan.chunk_target);
   }
   TS_LAUNCH_CHECK("attn_decode_merge");
   return TS_OK;

@@ -82,6 +82,28 @@ __device__ __forceinline__ uint4 ldg16_or_zero(const void* p, bool ok) {
 }
 __device__ __forceinline__ void stg16(void* p, uint4 v) { *reinterpret_cast<uint4*>(p) = v; }
 
+// Device-coherent 8-byte accesses (relaxed atomics at agent scope: they go through to the
+// memory side instead of staying in one XCD's L2).  Used for the partial results that one
+// workgroup writes and a workgroup on another XCD reads within the same launch; they avoid the
+// whole-L2 write-back / invalidate that an agent-scope fence costs.
+__device__ __forceinline__ void st_dev_f32x2(float* p, float a, float b) {
+  const uint64_t v = ((uint64_t)__float_as_uint(b) << 32) | __float_as_uint(a);
+  __hip_atomic_store(reinterpret_cast<uint64_t*>(p), v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ f32x2 ld_dev_f32x2(const float* p) {
+  const uint64_t v = __hip_atomic_load(reinterpret_cast<const uint64_t*>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  f32x2 r = {__uint_as_float((uint32_t)v), __uint_as_float((uint32_t)(v >> 32))};
+  return r;
+}
+__device__ __forceinline__ void st_dev_f32(float* p, float a) {
+  __hip_atomic_store(p, a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float ld_dev_f32(const float* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+// all of this wave's stores have been acknowledged (then a barrier covers the workgroup)
+__device__ __forceinline__ void wait_stores() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
 __device__ __forceinline__ float wave_sum(float v) {
 #pragma unroll
   for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
@@ -94,7 +116,10 @@ __device__ __forceinline__ float wave_max(float v) {
 }
 
 // ---- internal launchers (host), one per kernel family -----------------------
-int launch_rmsnorm(const ts_bf16* x, const ts_bf16* gamma, ts_bf16* y, int T, int H, float eps, hipStream_t s);
+// `zero`/`nzero`: optional int32 words the kernel clears on the side (the layer uses this to arm
+// the arrival counters of the kernels that follow on the same stream).
+int launch_rmsnorm(const ts_bf16* x, const ts_bf16* gamma, ts_bf16* y, int T, int H, float eps, hipStream_t s,
+                   int32_t* zero = nullptr, int nzero = 0);
 int launch_swiglu(const ts_bf16* gu, ts_bf16* out, int T, int F, hipStream_t s);
 int launch_rope(ts_bf16* q, ts_bf16* k, const ts_bf16* v, int q_stride, int kv_stride, const int32_t* pos,
                 const int32_t* seq_id, const float* cos_sin, int table_len, ts_bf16* kcache, ts_bf16* vcache,
@@ -111,9 +136,11 @@ int launch_moe_gemm(const ts_bf16* A, const int32_t* row_map, int row_div, const
                     const int32_t* offsets, ts_bf16* C, int rows, int E, int N, int K, hipStream_t s);
 
 size_t attention_decode_workspace_bytes(int B, int nq, int nkv, int d, int Lcap);
+// `counters` (optional): B * nkv zeroed int32 words; with them the chunk merge runs inside the
+// same launch (last chunk of a (sequence, kv head) to arrive), and the words are left zeroed.
 int launch_attention_decode(const ts_bf16* q, int q_stride, const ts_bf16* kc, const ts_bf16* vc, const int32_t* seq_lens,
                             ts_bf16* out, int B, int nq, int nkv, int d, int Lcap, float scale, void* ws,
-                            size_t ws_bytes, hipStream_t s);
+                            size_t ws_bytes, hipStream_t s, int32_t* counters = nullptr);
 int launch_attention_prefill(const ts_bf16* q, const ts_bf16* k, const ts_bf16* v, int q_stride, int kv_stride,
                              const int32_t* cu, ts_bf16* out, int S, int T, int max_seqlen, int nq, int nkv, int d,
                              float scale, int causal, hipStream_t s);

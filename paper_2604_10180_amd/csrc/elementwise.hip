@@ -9,9 +9,12 @@ namespace ts {
 // One workgroup per row; the row stays in registers between the reduction and the scaling.
 template <int VPT>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* __restrict__ x, const uint4* __restrict__ gamma,
-                                                      uint4* __restrict__ y, int H8, float eps, float inv_h) {
+                                                      uint4* __restrict__ y, int H8, float eps, float inv_h,
+                                                      int32_t* __restrict__ zero, int nzero) {
   const int row = blockIdx.x;
   const int tid = threadIdx.x;
+  if (row == 0)
+    for (int i = tid; i < nzero; i += 256) zero[i] = 0;
   const uint4* xr = x + (size_t)row * H8;
   U4 v[VPT];
   float ss = 0.f;
@@ -51,7 +54,8 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* __restrict__ 
   }
 }
 
-int launch_rmsnorm(const ts_bf16* x, const ts_bf16* gamma, ts_bf16* y, int T, int H, float eps, hipStream_t s) {
+int launch_rmsnorm(const ts_bf16* x, const ts_bf16* gamma, ts_bf16* y, int T, int H, float eps, hipStream_t s,
+                   int32_t* zero, int nzero) {
   if (T == 0) return TS_OK;
   const int H8 = H / 8;
   const int vpt = cdiv(H8, 256);
@@ -60,11 +64,11 @@ int launch_rmsnorm(const ts_bf16* x, const ts_bf16* gamma, ts_bf16* y, int T, in
   const uint4* gp = reinterpret_cast<const uint4*>(gamma);
   uint4* yp = reinterpret_cast<uint4*>(y);
   const float inv_h = 1.0f / (float)H;
-  if (vpt <= 1) TS_LAUNCH("rmsnorm", rmsnorm_kernel<1>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h);
-  else if (vpt <= 2) TS_LAUNCH("rmsnorm", rmsnorm_kernel<2>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h);
-  else if (vpt <= 4) TS_LAUNCH("rmsnorm", rmsnorm_kernel<4>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h);
-  else if (vpt <= 8) TS_LAUNCH("rmsnorm", rmsnorm_kernel<8>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h);
-  else TS_LAUNCH("rmsnorm", rmsnorm_kernel<16>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h);
+  if (vpt <= 1) TS_LAUNCH("rmsnorm", rmsnorm_kernel<1>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero);
+  else if (vpt <= 2) TS_LAUNCH("rmsnorm", rmsnorm_kernel<2>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero);
+  else if (vpt <= 4) TS_LAUNCH("rmsnorm", rmsnorm_kernel<4>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero);
+  else if (vpt <= 8) TS_LAUNCH("rmsnorm", rmsnorm_kernel<8>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero);
+  else TS_LAUNCH("rmsnorm", rmsnorm_kernel<16>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero);
   TS_LAUNCH_CHECK("rmsnorm");
   return TS_OK;
 }
