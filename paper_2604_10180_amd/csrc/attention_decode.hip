@@ -21,9 +21,10 @@ constexpr int kBlockKeys = 32;   // keys per wave iteration
 constexpr int kMinChunk = 2048;  // chunk size aimed at when splitting is not needed to fill the chip
 }
 
-// chunks of one sequence: as few as keep every chunk within chunk_target keys
+// chunks of one sequence: as few as keep every chunk within chunk_target keys (+ 1/16 slack, so
+// that a cache of 2^k positions plus the token being decoded is not split for one extra key)
 __host__ __device__ __forceinline__ int decode_nchunk(int len, int NCH, int chunk_target) {
-  int n = (len + chunk_target - 1) / chunk_target;
+  int n = (len - chunk_target / 16 + chunk_target - 1) / chunk_target;
   n = n < 1 ? 1 : n;
   return n < NCH ? n : NCH;
 }
