@@ -98,6 +98,51 @@ FAMILY_OF_LAUNCH = {
 }
 
 
+def time_pipeline(B, torch, wl, desc, dev_set, io_cpu, dev, steps, warmup):
+    """ts_pipeline_step over wl.n_micro micro-batches (index order), three ways: no boundary
+    copies, all boundaries copied on the side stream, all boundaries copied on the compute
+    streams.  Overlap holds when the second is about as fast as the first and faster than the
+    third (the method's requirement that communication hides behind computation, Sec. 3.3)."""
+    s, n_mb = wl.shape, wl.n_micro
+    per = wl.B // n_mb
+    wd, iod = dev_set[0], dev_set[1]
+    wts = dev_set[3]
+    outs = [torch.empty(per, s.H, dtype=torch.bfloat16, device=dev) for _ in range(n_mb)]
+    subs = []
+    for i in range(n_mb):
+        sl = slice(i * per, (i + 1) * per)
+        sub = {k: (v[sl] if k != "seq_id" else torch.arange(per, dtype=torch.int32, device=dev)) for k, v in iod.items()}
+        subs.append(sub)
+    mbs = [B.make_io(subs[i], outs[i], per, per) for i in range(n_mb)]
+    full = (1 << (B.TS_NB_MOE if s.E > 0 else B.TS_NB_DENSE)) - 1
+    stride = B.ts_pipeline_slot_stride(desc, per, per, full)
+    staging = torch.zeros(max(stride * n_mb, 16), dtype=torch.uint8, device=dev)
+    host = torch.zeros(max(stride * n_mb, 16), dtype=torch.uint8).pin_memory()
+    half = (B.ts_layer_workspace_bytes(desc, per, per) + 255) // 256 * 256
+    ws = torch.zeros(2 * half, dtype=torch.uint8, device=dev)
+    pipe = B.ts_pipeline_create(desc, n_mb)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    copy = torch.cuda.Stream()
+    out = {"micro_batches": n_mb, "sequences_per_micro_batch": per, "boundary_bytes_per_step": int(stride * n_mb)}
+    try:
+        for name, mask, serial in (("no_copies", 0, False), ("side_stream", full, False), ("serialised", full, True)):
+            def one():
+                B.ts_pipeline_step(pipe, wts, mbs, streams, copy, mask, staging, host, ws, copy_on_compute_stream=serial)
+            for _ in range(warmup):
+                one()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for _ in range(steps):
+                one()
+            torch.cuda.synchronize()
+            out[name + "_ms"] = round((time.perf_counter() - t0) * 1e3 / steps, 4)
+    finally:
+        B.ts_pipeline_destroy(pipe)
+    out["tokens_per_s_side_stream"] = round(wl.B / (out["side_stream_ms"] * 1e-3), 1)
+    out["overlap_ratio"] = round(out["side_stream_ms"] / out["no_copies_ms"], 4)
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -106,6 +151,9 @@ def main():
     ap.add_argument("--workload", default="8b_decode")
     ap.add_argument("--copies", type=int, default=2, help="rotated copies of weights+KV (defeats cache reuse across steps)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pipeline", action="store_true",
+                    help="also time ts_pipeline_step over the workload's micro-batches: boundary copies off, "
+                         "on the side stream, and serialised on the compute streams")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one 256 MiB elementwise copy (known traffic; used to scale rocprofv3 --pmc counters)")
     args = ap.parse_args()
@@ -218,6 +266,9 @@ def main():
         "sum_kernel_us": round(sum(k["avg_us"] for k in kernels), 1),
         "kernels": kernels,
     }
+
+    if args.pipeline and wl.mode == "decode" and wl.n_micro > 1:
+        result["pipeline"] = time_pipeline(B, torch, wl, desc, sets[0], io, dev, max(5, args.steps // 2), args.warmup)
 
     if not args.no_cpu_baseline:
         from oracle import decoder_layer as O

@@ -270,7 +270,9 @@ int ts_layer_forward(const ts_layer_desc* desc, const ts_layer_weights* w, const
  * bytes).  Slot i of dev_staging / pinned_host starts at i * slot_stride where
  * slot_stride = offsets[n] rounded up to 256.
  * dev_staging: device, >= n_mb*slot_stride bytes.  pinned_host: HOST pinned
- * memory of the same size.  ws: device, >= 2 * ts_layer_workspace_bytes(Tmax,Bmax)
+ * memory of the same size that the device can address (hipHostMalloc, or a
+ * torch tensor created with pin_memory): the pack kernel stores to it
+ * directly, no copy-engine command is issued.  ws: device, >= 2 * ts_layer_workspace_bytes(Tmax,Bmax)
  * rounded up to 256 each, where Tmax/Bmax are the largest over micro-batches.
  * All micro-batches must flag the same boundaries; their T may differ (the
  * layout is computed for each T; slot_stride uses the largest).

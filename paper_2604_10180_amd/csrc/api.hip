@@ -586,10 +586,8 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
         TS_HIP(hipStreamWaitEvent(copy, e, 0));
         target = copy;
       }
-      int r = launch_copy16(ptr, slot_dev + o, bytes, target);
-      if (r != TS_OK) return r;
-      TS_HIP(hipMemcpyAsync(slot_host + o, slot_dev + o, bytes, hipMemcpyDeviceToHost, target));
-      return TS_OK;
+      // one kernel packs the tensor into the device slot and stores it to the pinned host slot
+      return launch_copy16(ptr, slot_dev + o, bytes, target, slot_host + o);
     };
     rc = layer_forward_impl(d, *w, mb[i], wsh, s, hook);
     if (rc != TS_OK) return rc;

@@ -124,7 +124,7 @@ int launch_swiglu(const ts_bf16* gu, ts_bf16* out, int T, int F, hipStream_t s);
 int launch_rope(ts_bf16* q, ts_bf16* k, const ts_bf16* v, int q_stride, int kv_stride, const int32_t* pos,
                 const int32_t* seq_id, const float* cos_sin, int table_len, ts_bf16* kcache, ts_bf16* vcache,
                 int T, int nq, int nkv, int d, int Lcap, float base, hipStream_t s);
-int launch_copy16(const void* src, void* dst, size_t bytes, hipStream_t s);
+int launch_copy16(const void* src, void* dst, size_t bytes, hipStream_t s, void* dst2 = nullptr);
 
 size_t gemm_workspace_bytes(int M, int N, int K);
 int launch_gemm(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, void* C, bool f32out, int M, int N,

@@ -186,19 +186,34 @@ int launch_rope(ts_bf16* q, ts_bf16* k, const ts_bf16* v, int q_stride, int kv_s
 }
 
 // ---------------------------------------------------------------- boundary pack (contiguous copy)
-__global__ __launch_bounds__(256) void copy16_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst, size_t n16) {
+// Reads the boundary tensor once and writes it to the packed device slot and, when given, to the
+// device-mapped pinned host slot as well: the transfer is initiated by the kernel itself (the
+// analogue of the GPU-initiated sends of Sec. 4), with no copy-engine command whose cross-stream
+// dependency the runtime would resolve by blocking the launching host thread.
+__global__ __launch_bounds__(256) void copy16_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
+                                                     uint4* __restrict__ dst2, size_t n16) {
   size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * 256;
-  for (; i < n16; i += stride) dst[i] = src[i];
+  if (dst2 == nullptr) {
+    for (; i < n16; i += stride) dst[i] = src[i];
+  } else {
+    for (; i < n16; i += stride) {
+      const uint4 v = src[i];
+      dst[i] = v;
+      dst2[i] = v;
+    }
+  }
 }
 
-int launch_copy16(const void* src, void* dst, size_t bytes, hipStream_t s) {
+int launch_copy16(const void* src, void* dst, size_t bytes, hipStream_t s, void* dst2) {
   if (bytes == 0) return TS_OK;
   size_t n16 = bytes / 16;
   unsigned blocks = (unsigned)((n16 + 255) / 256);
-  if (blocks > 2048) blocks = 2048;
+  // few workgroups when the copy leaves over PCIe: it must not take CUs from the compute streams
+  const unsigned cap = dst2 != nullptr ? 32 : 2048;
+  if (blocks > cap) blocks = cap;
   TS_LAUNCH("copy16", copy16_kernel, dim3(blocks), dim3(256), 0, s, reinterpret_cast<const uint4*>(src),
-                     reinterpret_cast<uint4*>(dst), n16);
+            reinterpret_cast<uint4*>(dst), reinterpret_cast<uint4*>(dst2), n16);
   TS_LAUNCH_CHECK("copy16");
   return TS_OK;
 }

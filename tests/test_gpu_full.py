@@ -295,3 +295,23 @@ def test_70b_pipeline_full(B):
             return O.attention_decode(q, kc_i, vc_i, sub["seq_lens"], 1 / math.sqrt(s.d))
         st = check_stagewise(s, "decode", got, w64, sub["x"], sub["pos"], attn_ref, f"70b mb{i}")
         print(f"70b micro-batch {i}: lens={lens[i * per:(i + 1) * per]}\n   end-to-end vs exact: {e2e}\n   stage-wise: {st}")
+
+
+def test_70b_pipeline_boundary_copies_overlap(B):
+    """Sec. 3.3: the transfers of the boundary tensors hide behind the computation of the other
+    micro-batches.  Timed three ways on the 70B-shaped configuration (4 micro-batches of 8
+    sequences): no copies, all eight boundaries copied on the side stream, all copied on the
+    compute streams.  Wide margins: this is a timing test."""
+    import bench
+    wl = WL.CONFIGS["70b_pipeline"]
+    s = wl.shape
+    weights, io, _ = WL.build(wl)
+    Lcap = io["kcache"].shape[2]
+    desc = B.make_desc(s, Lcap, "decode")
+    wd = {k: v.to(DEV) for k, v in weights.items()}
+    iod = {k: v.to(DEV) for k, v in io.items()}
+    dev_set = (wd, iod, None, B.make_weights(wd), None)
+    r = bench.time_pipeline(B, torch, wl, desc, dev_set, io, DEV, steps=10, warmup=3)
+    print("70b pipeline step:", r)
+    assert r["side_stream_ms"] <= 1.15 * r["no_copies_ms"], r
+    assert r["side_stream_ms"] <= 1.03 * r["serialised_ms"], r
