@@ -278,8 +278,11 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
 template <int BM, int BN, bool F32OUT>
 __global__ __launch_bounds__(256) void gemm_tiled_kernel(const ts_bf16* __restrict__ A, const ts_bf16* __restrict__ W,
                                                          const ts_bf16* __restrict__ residual, void* __restrict__ C,
-                                                         int M, int N, int K, int tiles_m, int tiles_n) {
+                                                         int M, int N, int K, int tiles_m, int tiles_n,
+                                                         float* __restrict__ partial, int kslice) {
   constexpr int TN = BN / 64, TM = BM / 64;
+  // split-K: blockIdx.y owns K range [kbeg, kend) and writes an fp32 partial tile (partial != nullptr)
+  const int kbeg = blockIdx.y * kslice, kend = min(K, kbeg + kslice);
   constexpr int LW = BN / 32, LA = BM / 32;  // 16-byte chunks per thread per tile
   extern __shared__ uint4 smem[];
   // layout: [2][BN][9] then [2][BM][9]
@@ -321,14 +324,14 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const ts_bf16* __restri
 
   uint4 wr[LW], ar[LA];
   auto gload = [&](int k0) {
-    if (k0 + 64 <= K) {   // full K step: plain loads, nothing consumes them at issue time
+    if (k0 + 64 <= kend) {   // full K step: plain loads, nothing consumes them at issue time
 #pragma unroll
       for (int i = 0; i < LW; ++i) wr[i] = ldg16(wptr[i] + k0);
 #pragma unroll
       for (int i = 0; i < LA; ++i) ar[i] = ldg16(aptr[i] + k0);
     } else {
-      const bool ok = (k0 + st_c * 8) < K;
-      const int kk = ok ? k0 : 0;
+      const bool ok = (k0 + st_c * 8) < kend;
+      const int kk = ok ? k0 : kbeg;
 #pragma unroll
       for (int i = 0; i < LW; ++i) wr[i] = ldg16_or_zero(wptr[i] + kk, ok);
 #pragma unroll
@@ -342,13 +345,13 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const ts_bf16* __restri
     for (int i = 0; i < LA; ++i) sA[buf][st_r + 32 * i][st_c] = ar[i];
   };
 
-  gload(0);
+  gload(kbeg);
   sstore(0);
   __syncthreads();
   int it = 0;
-  for (int k0 = 0; k0 < K; k0 += 64, ++it) {
+  for (int k0 = kbeg; k0 < kend; k0 += 64, ++it) {
     const int cur = it & 1;
-    const bool more = (k0 + 64) < K;
+    const bool more = (k0 + 64) < kend;
     if (more) gload(k0 + 64);
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
@@ -380,6 +383,17 @@ __global__ __launch_bounds__(256) void gemm_tiled_kernel(const ts_bf16* __restri
         if (n >= N) continue;
         float v[4] = {acc[i][j][gi * 4 + 0], acc[i][j][gi * 4 + 1], acc[i][j][gi * 4 + 2], acc[i][j][gi * 4 + 3]};
         const size_t o = (size_t)m * N + n;
+        if (partial != nullptr) {
+          float* p = partial + (size_t)blockIdx.y * M * N + o;
+          if ((N & 3) == 0) {
+            *reinterpret_cast<f32x4*>(p) = f32x4{v[0], v[1], v[2], v[3]};
+          } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e)
+              if (n + e < N) p[e] = v[e];
+          }
+          continue;
+        }
         if (F32OUT) {
           float* p = reinterpret_cast<float*>(C) + o;
 #pragma unroll
@@ -488,27 +502,57 @@ void launch_skinny(const SkinnyArgs& a, int mrows, int NT, dim3 grid, hipStream_
 
 }  // namespace
 
+// Split of the 128 x 128-tile kernel along K for projections of a few hundred rows (a large
+// decode batch): 2 x 48 tiles leave most CUs idle and the weight stream at a fifth of the HBM
+// rate.  Slices until there are about 384 workgroups (512 measured slower); each slice keeps at least 512 of K.
+int plan_tiled_split(int M, int N, int K) {
+  const long tiles = (long)cdiv(M, 128) * cdiv(N, 128);
+  if (tiles >= 192) return 1;
+  int S = (int)((384 + tiles - 1) / tiles);
+  const int maxs = K / 512;
+  if (S > maxs) S = maxs;
+  if (S > 16) S = 16;
+  return S < 1 ? 1 : S;
+}
+
 template <int BM, int BN>
 int launch_tiled(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, void* C, bool f32out, int M, int N, int K,
-                 hipStream_t s) {
+                 hipStream_t s, int S = 1, float* partial = nullptr) {
   const int tiles_m = cdiv(M, BM), tiles_n = cdiv(N, BN);
   const size_t smem = (size_t)2 * (BM + BN) * 9 * sizeof(uint4);
-  dim3 grid(tiles_m * tiles_n);
+  const int kslice = (int)round_up((size_t)cdiv(K, S), 64);
+  S = cdiv(K, kslice);
+  if (S == 1) partial = nullptr;
+  dim3 grid(tiles_m * tiles_n, S);
   if (f32out) {
     allow_lds(gemm_tiled_kernel<BM, BN, true>, smem);
     TS_LAUNCH("gemm_tiled", (gemm_tiled_kernel<BM, BN, true>), grid, dim3(256), smem, s, A, W, residual, C, M, N, K,
-              tiles_m, tiles_n);
+              tiles_m, tiles_n, partial, kslice);
   } else {
     allow_lds(gemm_tiled_kernel<BM, BN, false>, smem);
     TS_LAUNCH("gemm_tiled", (gemm_tiled_kernel<BM, BN, false>), grid, dim3(256), smem, s, A, W, residual, C, M, N, K,
-              tiles_m, tiles_n);
+              tiles_m, tiles_n, partial, kslice);
   }
   TS_LAUNCH_CHECK("gemm_tiled");
+  if (partial != nullptr) {
+    const long MN = (long)M * N;
+    TS_LAUNCH("splitk_reduce", splitk_reduce_kernel, dim3((unsigned)((MN / 2 + 255) / 256)), dim3(256), 0, s, partial,
+              residual, C, MN, S, f32out ? 1 : 0);
+    TS_LAUNCH_CHECK("splitk_reduce");
+  }
   return TS_OK;
 }
 
+// the tiled 128 x 128 path is taken when neither the streaming kernel nor 256 x 256 tiles apply
+static bool use_tiled128(int M, int N) { return !use_skinny(M, N) && (long)cdiv(M, 256) * cdiv(N, 256) < 192; }
+
 size_t gemm_workspace_bytes(int M, int N, int K) {
-  if (M <= 0 || N <= 0 || K <= 0 || !use_skinny(M, N)) return 0;
+  if (M <= 0 || N <= 0 || K <= 0) return 0;
+  if (use_tiled128(M, N)) {
+    const int S = plan_tiled_split(M, N, K);
+    return S > 1 ? (size_t)S * M * N * sizeof(float) : 0;
+  }
+  if (!use_skinny(M, N)) return 0;
   SkinnyPlan p = plan_skinny(M, N, K);
   return p.S > 1 ? (size_t)p.S * M * N * sizeof(float) : 0;
 }
@@ -543,7 +587,11 @@ int launch_gemm(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, voi
       return launch_gemm_mfma256(A, W, residual, reinterpret_cast<ts_bf16*>(C), M, N, K, s);
     return launch_tiled<256, 256>(A, W, residual, C, f32out, M, N, K, s);
   }
-  return launch_tiled<128, 128>(A, W, residual, C, f32out, M, N, K, s);
+  const int S = plan_tiled_split(M, N, K);
+  const size_t need = S > 1 ? (size_t)S * M * N * sizeof(float) : 0;
+  TS_REQUIRE(need == 0 || (ws != nullptr && ws_bytes >= need), TS_ERR_WORKSPACE,
+             "ts_gemm_bf16: workspace %zu bytes < required %zu", ws_bytes, need);
+  return launch_tiled<128, 128>(A, W, residual, C, f32out, M, N, K, s, S, reinterpret_cast<float*>(ws));
 }
 
 int launch_moe_gemm(const ts_bf16* A, const int32_t* row_map, int row_div, const ts_bf16* W, const int32_t* offsets,

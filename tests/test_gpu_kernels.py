@@ -115,6 +115,7 @@ GEMM_SHAPES = [
     (100, 1376, 256), (17, 66, 72), (128, 130, 136),        # ragged M/N/K on the skinny kernel, N % 4 != 0
     (80, 320, 264), (96, 4096, 512), (256, 8, 4096),        # 96-row tile; tiny N loops over row blocks
     (130, 320, 264), (300, 1002, 520), (1024, 2048, 1024),  # tiled kernel with tails
+    (256, 6144, 4096), (200, 1002, 1544),                   # 128 x 128 tiles split along K (reduce kernel), with tails
     (4096, 4096, 128), (3900, 4104, 192), (3585, 3592, 64),  # 256 x 256 direct-to-LDS kernel: even/odd K steps, ragged M and N
 ]
 
