@@ -1,0 +1,134 @@
+"""CPU oracle for the kernel analyzer's dependency graph and the policy planner
+(TEST INFRASTRUCTURE, not product).
+
+Only tests/ may import this.  It shares no code with the C++ implementation in
+paper_2604_10180_amd/csrc/planner.hip and never imports it.
+
+What it is:
+
+* `ddg_build` -- the data-dependency graph of Sec. 3.1 ("Data dependency
+  analysis"), written as the definition: kernels are visited in execution
+  order, a read depends on the MOST RECENT earlier writer of the bytes it
+  reads (true, read-after-write dependencies only), a kernel never depends on
+  itself, one edge per (writer, reader) pair annotated with the bytes that
+  flow.  Cross-iteration dependencies are found the way the paper describes:
+  the kernel list is run for two iterations and a read in the second iteration
+  whose most recent writer ran in the first is flagged.
+* `policy_objective` / `plan_bruteforce` -- the two objectives of Sec. 3.2
+  evaluated literally from their formulas (placement variables x, computation
+  time T_g, communication time M_g with c = l + d / bw on cut edges, stage
+  time W_g = max(T_g, M_g); throughput objective min max_g W_g, latency
+  objective min sum t x + sum of c over cut edges) and minimised by
+  enumerating every placement.  Exponential on purpose.
+
+Readings taken (the paper leaves them open; listed in the design doc):
+  P1  an access is a byte range [addr, addr + extent) plus the number of bytes
+      actually touched inside it (`bytes <= extent`; the analyzer of Sec. 3.1
+      keeps a [min, max] hull per instruction).  The bytes that flow along a
+      dependency are min(overlap of the two ranges, bytes written, bytes read).
+  P2  several buffers between the same two kernels add up into one edge.
+  P3  all reads of a kernel happen before its writes.
+  P4  cross-iteration edges are reported separately and carry no cost in the
+      objectives (the method replicates such buffers and ships deltas in the
+      background, Sec. 4).
+  P5  M_g counts incoming cut edges only, as printed; the latency objective
+      counts every cut edge once.
+
+Pins (tests/test_planner_pins.py): hand-worked graphs and placements, closed
+forms (free communication, prohibitive communication, one GPU, balanced
+partition), and for two GPUs the latency objective against a max-flow/min-cut
+computed by scipy (the objective is a submodular two-label energy).
+No function here is "parity unpinned".
+"""
+from __future__ import annotations
+
+import itertools
+from typing import Dict, List, Sequence, Tuple
+
+Access = Tuple[int, int, int]          # (addr, extent, bytes touched)
+
+
+def _subtract(intervals: List[Tuple[int, int]], lo: int, hi: int) -> List[Tuple[int, int]]:
+    """Remove [lo, hi) from a list of disjoint half-open intervals."""
+    out = []
+    for a, b in intervals:
+        if hi <= a or b <= lo:
+            out.append((a, b))
+            continue
+        if a < lo:
+            out.append((a, lo))
+        if hi < b:
+            out.append((hi, b))
+    return out
+
+
+def ddg_build(kernels: Sequence[dict]):
+    """kernels[k] = {"reads": [Access...], "writes": [Access...]} in execution order.
+
+    Returns (edges, cross) where both are dicts {(writer, reader): bytes}; `edges` holds the
+    dependencies inside one iteration, `cross` those from the previous iteration.
+    """
+    n = len(kernels)
+    log: List[Tuple[int, int, int, int, int]] = []      # (iteration, kernel, addr, extent, bytes) of every write so far
+    edges: Dict[Tuple[int, int], int] = {}
+    cross: Dict[Tuple[int, int], int] = {}
+    for it in range(2):
+        for k in range(n):
+            for (addr, extent, nbytes) in kernels[k]["reads"]:
+                uncovered = [(addr, addr + extent)]
+                for (wit, wk, waddr, wext, wbytes) in reversed(log):   # most recent writer first
+                    if not uncovered:
+                        break
+                    ov = 0
+                    for a, b in uncovered:
+                        ov += max(0, min(b, waddr + wext) - max(a, waddr))
+                    if ov == 0:
+                        continue
+                    uncovered = _subtract(uncovered, waddr, waddr + wext)
+                    if wit == it and wk == k:
+                        continue                                        # a kernel does not depend on itself
+                    flow = min(ov, wbytes, nbytes)
+                    if it == 1:
+                        target = edges if wit == 1 else cross
+                        target[(wk, k)] = target.get((wk, k), 0) + flow
+            for (addr, extent, nbytes) in kernels[k]["writes"]:
+                log.append((it, k, addr, extent, nbytes))
+    return edges, cross
+
+
+def transfer_cost(d: float, u: int, g: int, bw, lat) -> float:
+    """c_ij^{u,g} = l_{u,g} + d_ij / bw_{u,g}."""
+    return lat[u][g] + d / bw[u][g]
+
+
+def policy_terms(place: Sequence[int], t, edges: Dict[Tuple[int, int], float], bw, lat, n_gpus: int):
+    """(T_g, M_g) of a placement: computation and incoming-communication time per GPU."""
+    T = [0.0] * n_gpus
+    M = [0.0] * n_gpus
+    for k, g in enumerate(place):
+        T[g] += t[k][g]
+    for (i, j), d in edges.items():
+        u, g = place[i], place[j]
+        if u != g:
+            M[g] += transfer_cost(d, u, g, bw, lat)
+    return T, M
+
+
+def policy_objective(place, t, edges, bw, lat, n_gpus: int, objective: str) -> float:
+    T, M = policy_terms(place, t, edges, bw, lat, n_gpus)
+    if objective == "throughput":
+        return max(max(T[g], M[g]) for g in range(n_gpus))
+    if objective == "latency":
+        return sum(T) + sum(M)
+    raise ValueError(objective)
+
+
+def plan_bruteforce(t, edges, bw, lat, objective: str):
+    """Enumerate every placement; returns (best objective value, one best placement)."""
+    n_k, n_g = len(t), len(t[0])
+    best, best_place = None, None
+    for place in itertools.product(range(n_g), repeat=n_k):
+        v = policy_objective(place, t, edges, bw, lat, n_g, objective)
+        if best is None or v < best:
+            best, best_place = v, place
+    return best, list(best_place)
