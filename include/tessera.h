@@ -288,6 +288,99 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
                      void* compute_streams[2], void* copy_stream, uint64_t boundary_mask,
                      int copy_on_compute_stream, void* dev_staging, void* pinned_host,
                      size_t staging_bytes, void* ws, size_t ws_bytes);
+
+/* ---------------------------------------------------------------------------
+ * Kernel analyzer: data-dependency graph (Sec. 3.1, "Data dependency analysis").
+ * HOST-only: every pointer below is host memory, nothing touches the GPU.
+ *
+ * A kernel is described by the byte ranges it reads and writes.  An access is
+ * the hull [addr, addr + extent) of what the kernel touches in one buffer plus
+ * the number of bytes it really touches inside it (bytes <= extent; a strided
+ * or indexed access has bytes < extent).  iter_advance is the number of bytes
+ * the range moves forward from one iteration to the next (0 for ordinary
+ * buffers; one cache position for the append of a decode step).
+ *
+ * ts_ddg_build visits the kernels in execution order for two consecutive
+ * iterations, keeping for every byte its last writer.  A read adds an edge from
+ * the most recent writer of each part of its range (read-after-write only; a
+ * kernel reads before it writes and never depends on itself); the bytes on the
+ * edge are min(overlap, bytes written, bytes read), summed over the buffers
+ * shared by the two kernels.  Edges found in the second iteration whose writer
+ * ran in the first have cross_iteration = 1.
+ * Output: edges[0..*n_edges), intra-iteration edges first, each group sorted by
+ * (src, dst).  If more than max_edges exist, *n_edges is the number needed and
+ * TS_ERR_WORKSPACE is returned with nothing written to edges.
+ */
+typedef struct ts_access {
+  uint64_t addr, extent, bytes;
+  int64_t iter_advance;
+} ts_access;
+typedef struct ts_kernel_io {
+  const ts_access* reads;
+  const ts_access* writes;
+  int32_t n_reads, n_writes;
+} ts_kernel_io;
+typedef struct ts_ddg_edge {
+  int32_t src, dst;          /* kernel indices, src is the writer */
+  uint64_t bytes;
+  int32_t cross_iteration;   /* 1: the value comes from the previous iteration */
+  int32_t reserved;
+} ts_ddg_edge;
+int ts_ddg_build(const ts_kernel_io* kernels, int n_kernels, ts_ddg_edge* edges, int max_edges,
+                 int* n_edges);
+
+/* The dependency graph of n_layers decoder layers of `desc` at T tokens / B
+ * sequences, built by ts_ddg_build from the buffers ts_layer_forward really
+ * uses (workspace offsets of the kernel boundaries, the routing tables of a MoE
+ * layer, the residual input, the KV caches).  A node is the group of kernels
+ * that ends at one kernel boundary, so node (layer * NB + i) produces boundary
+ * i of that layer (NB = TS_NB_DENSE or TS_NB_MOE); ts_layer_node_name names it.
+ * Decode: the cache append is modelled row by row with iter_advance = one
+ * position, kv_len = keys each sequence attends (>= 1), so the cache shows up
+ * as a cross-iteration edge carrying one iteration's new K/V rows.  Prefill:
+ * attention reads K/V from the projection output and kv_len is ignored.
+ * Weights are never written and are left out.  Same output rules as ts_ddg_build.
+ */
+int ts_layer_ddg(const ts_layer_desc* desc, int T, int B, int kv_len, int n_layers,
+                 ts_ddg_edge* edges, int max_edges, int* n_edges);
+const char* ts_layer_node_name(const ts_layer_desc* desc, int node_in_layer);
+/* boundary_mask for ts_pipeline_step from a placement of one layer's nodes:
+ * placement[i] is the GPU of node i, placement[NB] the GPU that consumes the
+ * layer's output.  Bit i is set when some consumer of boundary i sits on
+ * another GPU than its producer.  TS_ERR_UNSUPPORTED_SHAPE if the placement
+ * separates kernels that exchange data outside the kernel boundaries (the
+ * routing tables of a MoE layer). */
+int ts_layer_cut_mask(const ts_layer_desc* desc, const int32_t* placement, uint64_t* boundary_mask);
+
+/* ---------------------------------------------------------------------------
+ * Policy planner (Sec. 3.2).  HOST-only.
+ * Chooses placement[k] in [0, n_gpus) for every kernel so as to minimise
+ *   TS_PLAN_THROUGHPUT:  max_g max(T_g, M_g)      (the slowest pipeline stage)
+ *   TS_PLAN_LATENCY:     sum_g T_g + sum_g M_g    (every kernel and every cut edge once)
+ * with T_g = sum of t[k][g] over kernels placed on g and M_g = sum over edges
+ * (i, j) with j on g and i on u != g of lat[u][g] + bytes / bw[u][g].
+ * t: [n_kernels][n_gpus] seconds; bw: [n_gpus][n_gpus] bytes/s; lat: same
+ * shape, seconds (diagonals ignored; both may be NULL when n_gpus == 1).
+ * Edges must satisfy src < dst; edges with cross_iteration != 0 are ignored
+ * (such buffers are replicated and their deltas shipped in the background).
+ * The latency objective is solved exactly.  The throughput objective is solved
+ * by branch and bound, exactly unless more than node_limit search nodes are
+ * needed (node_limit <= 0: 5e7); then the best placement found is returned and
+ * *proved_optimal = 0.  T_g, M_g (each [n_gpus]) and proved_optimal may be NULL.
+ * Ties between optimal placements are broken arbitrarily.
+ */
+#define TS_PLAN_THROUGHPUT 0
+#define TS_PLAN_LATENCY 1
+typedef struct ts_plan_problem {
+  int32_t n_kernels, n_gpus, n_edges, reserved;
+  const double* t;
+  const ts_ddg_edge* edges;
+  const double* bw;
+  const double* lat;
+} ts_plan_problem;
+int ts_plan_policy(const ts_plan_problem* problem, int objective, int64_t node_limit,
+                   int32_t* placement, double* value, double* T_g, double* M_g,
+                   int* proved_optimal);
 #if defined(__GNUC__)
 #pragma GCC visibility pop
 #endif

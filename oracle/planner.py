@@ -33,6 +33,10 @@ Readings taken (the paper leaves them open; listed in the design doc):
       background, Sec. 4).
   P5  M_g counts incoming cut edges only, as printed; the latency objective
       counts every cut edge once.
+  P6  the two profiled iterations of Sec. 3.1 are consecutive real iterations:
+      an append-style access (the KV cache row of the token being decoded)
+      lands one position further in the second iteration.  An access may carry
+      a fourth element, the bytes its range advances per iteration (default 0).
 
 Pins (tests/test_planner_pins.py): hand-worked graphs and placements, closed
 forms (free communication, prohibitive communication, one GPU, balanced
@@ -45,7 +49,14 @@ from __future__ import annotations
 import itertools
 from typing import Dict, List, Sequence, Tuple
 
-Access = Tuple[int, int, int]          # (addr, extent, bytes touched)
+Access = Tuple[int, ...]               # (addr, extent, bytes touched[, advance per iteration])
+
+
+def _at(access, it: int):
+    """The access as it happens in iteration `it` (reading P6)."""
+    addr, extent, nbytes = access[:3]
+    step = access[3] if len(access) > 3 else 0
+    return addr + it * step, extent, nbytes
 
 
 def _subtract(intervals: List[Tuple[int, int]], lo: int, hi: int) -> List[Tuple[int, int]]:
@@ -74,7 +85,8 @@ def ddg_build(kernels: Sequence[dict]):
     cross: Dict[Tuple[int, int], int] = {}
     for it in range(2):
         for k in range(n):
-            for (addr, extent, nbytes) in kernels[k]["reads"]:
+            for access in kernels[k]["reads"]:
+                addr, extent, nbytes = _at(access, it)
                 uncovered = [(addr, addr + extent)]
                 for (wit, wk, waddr, wext, wbytes) in reversed(log):   # most recent writer first
                     if not uncovered:
@@ -91,7 +103,8 @@ def ddg_build(kernels: Sequence[dict]):
                     if it == 1:
                         target = edges if wit == 1 else cross
                         target[(wk, k)] = target.get((wk, k), 0) + flow
-            for (addr, extent, nbytes) in kernels[k]["writes"]:
+            for access in kernels[k]["writes"]:
+                addr, extent, nbytes = _at(access, it)
                 log.append((it, k, addr, extent, nbytes))
     return edges, cross
 

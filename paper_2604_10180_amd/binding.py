@@ -26,7 +26,7 @@ EXPORTS = [
     "ts_attention_decode", "ts_attention_prefill", "ts_swiglu", "ts_moe_route", "ts_moe_gemm", "ts_moe_combine",
     "ts_layer_workspace_bytes", "ts_layer_boundary", "ts_layer_moe_buffers", "ts_layer_forward",
     "ts_pipeline_create", "ts_pipeline_destroy", "ts_pipeline_boundary_layout", "ts_pipeline_slot_stride",
-    "ts_pipeline_step",
+    "ts_pipeline_step", "ts_ddg_build", "ts_layer_ddg", "ts_layer_node_name", "ts_layer_cut_mask", "ts_plan_policy",
 ]
 
 
@@ -52,6 +52,29 @@ class LayerIO(C.Structure):
                [("T", C.c_int32), ("B", C.c_int32), ("max_seqlen", C.c_int32)]
 
 
+class Access(C.Structure):
+    _fields_ = [("addr", C.c_uint64), ("extent", C.c_uint64), ("bytes", C.c_uint64), ("iter_advance", C.c_int64)]
+
+
+class KernelIO(C.Structure):
+    _fields_ = [("reads", C.POINTER(Access)), ("writes", C.POINTER(Access)), ("n_reads", C.c_int32),
+                ("n_writes", C.c_int32)]
+
+
+class DdgEdge(C.Structure):
+    _fields_ = [("src", C.c_int32), ("dst", C.c_int32), ("bytes", C.c_uint64), ("cross_iteration", C.c_int32),
+                ("reserved", C.c_int32)]
+
+
+class PlanProblem(C.Structure):
+    _fields_ = [("n_kernels", C.c_int32), ("n_gpus", C.c_int32), ("n_edges", C.c_int32), ("reserved", C.c_int32),
+                ("t", C.POINTER(C.c_double)), ("edges", C.POINTER(DdgEdge)), ("bw", C.POINTER(C.c_double)),
+                ("lat", C.POINTER(C.c_double))]
+
+
+TS_PLAN_THROUGHPUT, TS_PLAN_LATENCY = 0, 1
+
+
 def _load() -> C.CDLL:
     if not os.path.exists(LIB_PATH):
         raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2604_10180_amd.build` "
@@ -63,6 +86,7 @@ def _load() -> C.CDLL:
               "ts_pipeline_slot_stride"):
         getattr(lib, n).restype = C.c_size_t
     lib.ts_pipeline_destroy.restype = None
+    lib.ts_layer_node_name.restype = C.c_char_p
     return lib
 
 
@@ -95,6 +119,12 @@ lib.ts_pipeline_boundary_layout.argtypes = [C.POINTER(LayerDesc), _i, _i, _u64, 
 lib.ts_pipeline_slot_stride.argtypes = [C.POINTER(LayerDesc), _i, _i, _u64]
 lib.ts_pipeline_step.argtypes = [_p, C.POINTER(LayerWeights), C.POINTER(LayerIO), _i, C.POINTER(_p), _p, _u64, _i,
                                  _p, _p, _z, _p, _z]
+lib.ts_ddg_build.argtypes = [C.POINTER(KernelIO), _i, C.POINTER(DdgEdge), _i, C.POINTER(_i)]
+lib.ts_layer_ddg.argtypes = [C.POINTER(LayerDesc), _i, _i, _i, _i, C.POINTER(DdgEdge), _i, C.POINTER(_i)]
+lib.ts_layer_node_name.argtypes = [C.POINTER(LayerDesc), _i]
+lib.ts_layer_cut_mask.argtypes = [C.POINTER(LayerDesc), C.POINTER(C.c_int32), C.POINTER(_u64)]
+lib.ts_plan_policy.argtypes = [C.POINTER(PlanProblem), _i, C.c_int64, C.POINTER(C.c_int32), C.POINTER(C.c_double),
+                               C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(_i)]
 
 
 def _ptr(t) -> Optional[int]:
@@ -266,6 +296,72 @@ def ts_pipeline_step(handle: int, weights: LayerWeights, mbs: Sequence[LayerIO],
     _check(lib.ts_pipeline_step(handle, C.byref(weights), arr, len(mbs), cs, _stream(copy_stream),
                                 mask & (2 ** 64 - 1), 1 if copy_on_compute_stream else 0, _ptr(dev_staging),
                                 _ptr(pinned_host), _nbytes(dev_staging), _ptr(ws), _nbytes(ws)))
+
+
+def _edges_out(call):
+    """Run an edge-producing call, growing the edge array until it fits.  Returns [(src, dst, bytes, cross)]."""
+    cap = 256
+    while True:
+        arr, n = (DdgEdge * cap)(), _i()
+        rc = call(arr, cap, C.byref(n))
+        if rc == TS_ERR_WORKSPACE and n.value > cap:
+            cap = n.value
+            continue
+        _check(rc)
+        return [(arr[i].src, arr[i].dst, arr[i].bytes, arr[i].cross_iteration) for i in range(n.value)]
+
+
+def _access_array(accesses):
+    arr = (Access * max(1, len(accesses)))()
+    for i, a in enumerate(accesses):
+        arr[i] = Access(a[0], a[1], a[2], a[3] if len(a) > 3 else 0)
+    return arr
+
+
+def ts_ddg_build(kernels):
+    """kernels[k] = {"reads": [(addr, extent, bytes[, iter_advance])...], "writes": [...]} in execution order."""
+    keep = []
+    ks = (KernelIO * max(1, len(kernels)))()
+    for i, k in enumerate(kernels):
+        r, w = _access_array(k["reads"]), _access_array(k["writes"])
+        keep += [r, w]
+        ks[i] = KernelIO(r, w, len(k["reads"]), len(k["writes"]))
+    return _edges_out(lambda arr, cap, n: lib.ts_ddg_build(ks, len(kernels), arr, cap, n))
+
+
+def ts_layer_ddg(desc: LayerDesc, T: int, B: int, kv_len: int, n_layers: int = 1):
+    return _edges_out(lambda arr, cap, n: lib.ts_layer_ddg(C.byref(desc), T, B, kv_len, n_layers, arr, cap, n))
+
+
+def ts_layer_node_name(desc: LayerDesc, node: int) -> Optional[str]:
+    r = lib.ts_layer_node_name(C.byref(desc), node)
+    return None if r is None else r.decode()
+
+
+def ts_layer_cut_mask(desc: LayerDesc, placement: Sequence[int]) -> int:
+    nb = TS_NB_MOE if desc.E > 0 else TS_NB_DENSE
+    if len(placement) != nb + 1:
+        raise ValueError(f"placement needs {nb + 1} entries (the layer's nodes, then the consumer of its output)")
+    arr, mask = (C.c_int32 * (nb + 1))(*placement), _u64()
+    _check(lib.ts_layer_cut_mask(C.byref(desc), arr, C.byref(mask)))
+    return mask.value
+
+
+def ts_plan_policy(t, edges, bw, lat, objective: int, node_limit: int = 0):
+    """t: [K][G] seconds; edges: [(src, dst, bytes[, cross])]; bw, lat: [G][G].
+    Returns (placement, value, T_g, M_g, proved_optimal)."""
+    K, G = len(t), len(t[0])
+    flat = lambda m: (C.c_double * (len(m) * len(m[0])))(*[float(v) for row in m for v in row])
+    ta = flat(t)
+    ea = (DdgEdge * max(1, len(edges)))()
+    for i, e in enumerate(edges):
+        ea[i] = DdgEdge(e[0], e[1], int(e[2]), e[3] if len(e) > 3 else 0, 0)
+    prob = PlanProblem(K, G, len(edges), 0, ta, ea, flat(bw) if bw is not None else None,
+                       flat(lat) if lat is not None else None)
+    place, val, opt = (C.c_int32 * K)(), C.c_double(), _i()
+    Tg, Mg = (C.c_double * G)(), (C.c_double * G)()
+    _check(lib.ts_plan_policy(C.byref(prob), objective, node_limit, place, C.byref(val), Tg, Mg, C.byref(opt)))
+    return list(place), val.value, list(Tg), list(Mg), bool(opt.value)
 
 
 class KernelProfile:

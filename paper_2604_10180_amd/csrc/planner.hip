@@ -1,0 +1,561 @@
+// Host side of the method around the kernels: the kernel analyzer's data-dependency graph
+// (Sec. 3.1, "Data dependency analysis") and the policy planner (Sec. 3.2).  No device code.
+//
+// Dependency graph: kernels are visited in execution order against a registry of the last
+// writer of every byte (an ordered map of disjoint intervals); a read adds an edge from the
+// most recent writer of each piece it overlaps, a kernel never depends on itself, edges between
+// the same two kernels are merged.  The list is run for two iterations; a read of the second
+// iteration that is served by a write of the first is a cross-iteration dependency (the KV
+// cache pattern), reported with its flag set.
+//
+// Planner: both objectives of Sec. 3.2 over placements x[k] in G,
+//   T_g = sum_k t[k][g] [x_k = g],  M_g = sum over edges (i,j) cut into g of (l[u][g] + d_ij / bw[u][g]),
+//   throughput:  min max_g max(T_g, M_g)        latency:  min sum_g T_g + sum_g M_g.
+// The paper hands the linearised MILP to a commercial solver; here the latency objective is
+// solved exactly by dynamic programming over the frontier of kernels whose outputs are still
+// needed (a decoder stack keeps that frontier at two or three kernels, so 500 kernels take
+// microseconds), and the throughput objective by depth-first branch and bound in execution order
+// (T_g and M_g only grow along a branch, so max_g max(T_g, M_g) and the average-load bound
+// prune), exact unless the node limit stops it.
+#include <algorithm>
+#include <cmath>
+#include <limits>
+#include <map>
+#include <unordered_map>
+#include <utility>
+#include <vector>
+
+#include "common.hpp"
+
+namespace ts {
+namespace {
+
+struct WriteInst {       // one write access of one kernel launch
+  int writer, iter;
+  uint64_t bytes;        // bytes that write actually touched inside its hull
+};
+struct Piece {           // registry entry: bytes [lo, hi) were last written by write instance `wid`
+  uint64_t hi;
+  int wid;
+};
+
+using Registry = std::map<uint64_t, Piece>;   // key = lo
+
+void registry_write(Registry& reg, uint64_t lo, uint64_t hi, int wid) {
+  if (hi <= lo) return;
+  auto it = reg.lower_bound(lo);
+  if (it != reg.begin()) {
+    auto pv = std::prev(it);
+    if (pv->second.hi > lo) {                       // split the piece that straddles lo
+      Piece tail = pv->second;
+      pv->second.hi = lo;
+      if (tail.hi > hi) reg[hi] = tail;             // ... and survives beyond hi
+    }
+  }
+  while (it != reg.end() && it->first < hi) {
+    if (it->second.hi > hi) {                       // keep the part beyond hi
+      Piece tail = it->second;
+      reg.erase(it);
+      reg[hi] = tail;
+      break;
+    }
+    it = reg.erase(it);
+  }
+  reg[lo] = Piece{hi, wid};
+}
+
+struct EdgeKey {
+  int src, dst, cross;
+  bool operator<(const EdgeKey& o) const {
+    if (cross != o.cross) return cross < o.cross;
+    if (src != o.src) return src < o.src;
+    return dst < o.dst;
+  }
+};
+
+int ddg_build_impl(const ts_kernel_io* ks, int n, std::vector<ts_ddg_edge>& out) {
+  Registry reg;
+  std::vector<WriteInst> inst;
+  std::map<EdgeKey, uint64_t> acc;
+  std::map<int, uint64_t> ov;                       // write instance -> bytes of this read it still owns
+  for (int iter = 0; iter < 2; ++iter) {
+    for (int k = 0; k < n; ++k) {
+      for (int r = 0; r < ks[k].n_reads; ++r) {
+        if (iter == 0) break;                       // the first iteration only fills the registry
+        const ts_access& a = ks[k].reads[r];
+        const uint64_t lo = a.addr + (uint64_t)(a.iter_advance * iter), hi = lo + a.extent;
+        if (hi <= lo) continue;
+        ov.clear();
+        auto it = reg.upper_bound(lo);
+        if (it != reg.begin()) --it;
+        for (; it != reg.end() && it->first < hi; ++it) {
+          const uint64_t a0 = std::max(lo, it->first), a1 = std::min(hi, it->second.hi);
+          if (a1 > a0) ov[it->second.wid] += a1 - a0;
+        }
+        for (const auto& kv : ov) {
+          const WriteInst& w = inst[kv.first];
+          if (w.iter == iter && w.writer == k) continue;
+          const uint64_t flow = std::min(std::min(kv.second, w.bytes), (uint64_t)a.bytes);
+          acc[EdgeKey{w.writer, k, w.iter == iter ? 0 : 1}] += flow;
+        }
+      }
+      for (int w = 0; w < ks[k].n_writes; ++w) {
+        const ts_access& a = ks[k].writes[w];
+        const uint64_t lo = a.addr + (uint64_t)(a.iter_advance * iter);
+        inst.push_back(WriteInst{k, iter, a.bytes});
+        registry_write(reg, lo, lo + a.extent, (int)inst.size() - 1);
+      }
+    }
+  }
+  out.clear();
+  for (const auto& kv : acc) {
+    ts_ddg_edge e{};
+    e.src = kv.first.src;
+    e.dst = kv.first.dst;
+    e.bytes = kv.second;
+    e.cross_iteration = kv.first.cross;
+    out.push_back(e);
+  }
+  return TS_OK;
+}
+
+// ---------------------------------------------------------------------------- planner
+struct Problem {
+  int K, G;
+  const double* t;
+  std::vector<std::vector<std::pair<int, double>>> in;   // per kernel: (producer, bytes) of intra-iteration edges
+  const double *bw, *lat;
+  double cost(int u, int g, double d) const { return lat[u * G + g] + d / bw[u * G + g]; }
+};
+
+void evaluate(const Problem& p, const int32_t* place, std::vector<double>& T, std::vector<double>& M) {
+  T.assign(p.G, 0.0);
+  M.assign(p.G, 0.0);
+  for (int k = 0; k < p.K; ++k) {
+    const int g = place[k];
+    T[g] += p.t[k * p.G + g];
+    for (const auto& e : p.in[k]) {
+      const int u = place[e.first];
+      if (u != g) M[g] += p.cost(u, g, e.second);
+    }
+  }
+}
+
+// Latency objective: exact frontier DP.  State = placement of the kernels that still have a consumer ahead.
+bool plan_latency_dp(const Problem& p, std::vector<int32_t>& best_place, double& best) {
+  const int K = p.K, G = p.G;
+  std::vector<int> last_use(K, -1);
+  for (int k = 0; k < K; ++k)
+    for (const auto& e : p.in[k]) last_use[e.first] = std::max(last_use[e.first], k);
+  int bits = 1;
+  while ((1 << bits) < G) ++bits;
+  // live list before kernel k, in ascending kernel order
+  std::vector<std::vector<int>> live(K + 1);
+  for (int k = 0; k < K; ++k) {
+    live[k + 1] = live[k];
+    live[k + 1].erase(std::remove_if(live[k + 1].begin(), live[k + 1].end(), [&](int i) { return last_use[i] <= k; }),
+                      live[k + 1].end());
+    if (last_use[k] > k) live[k + 1].push_back(k);
+    if ((int)live[k + 1].size() * bits > 60) return false;   // frontier too wide for this encoding
+  }
+  struct Entry { double cost; uint64_t prev; int g; };
+  std::vector<std::unordered_map<uint64_t, Entry>> layers(K + 1);
+  layers[0][0] = Entry{0.0, 0, -1};
+  for (int k = 0; k < K; ++k) {
+    const auto& lv = live[k];
+    const auto& nx = live[k + 1];
+    for (const auto& kv : layers[k]) {
+      const uint64_t st = kv.first;
+      auto placed = [&](int i) {
+        const int pos = (int)(std::find(lv.begin(), lv.end(), i) - lv.begin());
+        return (int)((st >> (pos * bits)) & ((1u << bits) - 1));
+      };
+      for (int g = 0; g < G; ++g) {
+        double c = kv.second.cost + p.t[k * G + g];
+        for (const auto& e : p.in[k]) {
+          const int u = placed(e.first);
+          if (u != g) c += p.cost(u, g, e.second);
+        }
+        uint64_t ns = 0;
+        for (size_t q = 0; q < nx.size(); ++q) {
+          const int pl = nx[q] == k ? g : placed(nx[q]);
+          ns |= (uint64_t)pl << (q * bits);
+        }
+        auto it = layers[k + 1].find(ns);
+        if (it == layers[k + 1].end() || c < it->second.cost) layers[k + 1][ns] = Entry{c, st, g};
+      }
+    }
+  }
+  best = std::numeric_limits<double>::infinity();
+  uint64_t st = 0;
+  for (const auto& kv : layers[K])
+    if (kv.second.cost < best) { best = kv.second.cost; st = kv.first; }
+  best_place.assign(K, 0);
+  for (int k = K; k > 0; --k) {
+    const Entry& e = layers[k].at(st);
+    best_place[k - 1] = e.g;
+    st = e.prev;
+  }
+  return true;
+}
+
+// Incumbent for the search: the best split of the execution order into G contiguous stages (stage g on GPU g,
+// stages may be empty), by dynamic programming with every incoming edge priced as if it came from the
+// previous GPU.  Only a starting point: the caller evaluates it exactly.
+void contiguous_seed(const Problem& p, std::vector<int32_t>& place) {
+  const int K = p.K, G = p.G;
+  const double inf = std::numeric_limits<double>::infinity();
+  std::vector<std::vector<double>> f(G + 1, std::vector<double>(K + 1, inf));
+  std::vector<std::vector<int>> from(G + 1, std::vector<int>(K + 1, 0));
+  f[0][0] = 0.0;
+  for (int g = 1; g <= G; ++g) {
+    const int dev = g - 1, src = g >= 2 ? g - 2 : 0;
+    for (int a = 0; a <= K; ++a) {
+      if (f[g - 1][a] == inf) continue;
+      double T = 0.0, M = 0.0;
+      for (int b = a; b <= K; ++b) {
+        if (b > a) {
+          const int k = b - 1;
+          T += p.t[k * G + dev];
+          if (dev != src)
+            for (const auto& e : p.in[k])
+              if (e.first < a) M += p.cost(src, dev, e.second);
+        }
+        const double c = std::max(f[g - 1][a], std::max(T, M));
+        if (c < f[g][b]) { f[g][b] = c; from[g][b] = a; }
+      }
+    }
+  }
+  place.assign(K, 0);
+  int b = K;
+  for (int g = G; g >= 1; --g) {
+    const int a = from[g][b];
+    for (int k = a; k < b; ++k) place[k] = g - 1;
+    b = a;
+  }
+}
+
+struct BnB {
+  const Problem& p;
+  int objective;
+  int64_t node_limit, nodes = 0;
+  bool exhausted = false;
+  std::vector<double> T, M, rem_min;          // rem_min[k] = sum_{j >= k} min_g t[j][g]
+  std::vector<int32_t> place, best_place;
+  double best = std::numeric_limits<double>::infinity();
+
+  double bound(int k) const {                 // lower bound of any completion with kernels < k placed
+    if (objective == TS_PLAN_LATENCY) {
+      double s = rem_min[k];
+      for (int g = 0; g < p.G; ++g) s += T[g] + M[g];
+      return s;
+    }
+    double mx = 0.0, sum = rem_min[k];
+    for (int g = 0; g < p.G; ++g) {
+      mx = std::max(mx, std::max(T[g], M[g]));
+      sum += T[g];
+    }
+    return std::max(mx, sum / p.G);
+  }
+  void dfs(int k) {
+    if (exhausted) return;
+    if (++nodes > node_limit) { exhausted = true; return; }
+    if (k == p.K) {
+      const double v = bound(k);
+      if (v < best) { best = v; best_place = place; }
+      return;
+    }
+    // children ordered by their bound
+    std::vector<std::pair<double, int>> order;
+    std::vector<double> dT(p.G), dM(p.G);
+    for (int g = 0; g < p.G; ++g) {
+      dT[g] = p.t[k * p.G + g];
+      dM[g] = 0.0;
+      for (const auto& e : p.in[k]) {
+        const int u = place[e.first];
+        if (u != g) dM[g] += p.cost(u, g, e.second);
+      }
+      T[g] += dT[g]; M[g] += dM[g];
+      order.push_back({bound(k + 1), g});
+      T[g] -= dT[g]; M[g] -= dM[g];
+    }
+    std::sort(order.begin(), order.end());
+    for (const auto& o : order) {
+      if (o.first >= best) break;
+      const int g = o.second;
+      const double t0 = T[g], m0 = M[g];
+      T[g] += dT[g]; M[g] += dM[g];
+      place[k] = g;
+      dfs(k + 1);
+      T[g] = t0; M[g] = m0;                    // restore exactly (no accumulated rounding)
+    }
+  }
+};
+
+
+// ---------------------------------------------------------------------------- the layer as a kernel list
+// Nodes = kernel groups ending at a kernel boundary (node i writes boundary i).  Addresses: the workspace at
+// its real offsets (all layers share it, as they do at run time), then per layer the residual stream and
+// the two caches in a synthetic region above it.
+struct LayerNodes {
+  std::vector<std::vector<ts_access>> reads, writes;
+  std::vector<ts_kernel_io> io;
+};
+
+constexpr int kBoundaryBuffers = 1, kSideTables = 2;
+
+int build_layer_nodes(const ts_layer_desc& d, int T, int B, int kv_len, int n_layers, int which, LayerNodes& out) {
+  const bool moe = d.E > 0;
+  const int nb = moe ? TS_NB_MOE : TS_NB_DENSE;
+  const uint64_t WS = 4096;
+  const uint64_t ws_bytes = (uint64_t)ts_layer_workspace_bytes(&d, T, B);
+  const uint64_t xbytes = (uint64_t)T * d.H * 2;
+  const uint64_t cache_bytes = (uint64_t)B * d.nkv * d.Lcap * d.d * 2;
+  auto up = [](uint64_t v) { return (v + 4095) / 4096 * 4096; };
+  const uint64_t EXT = WS + up(ws_bytes) + 4096;
+  const uint64_t per_layer = up(xbytes) + 2 * up(cache_bytes);
+  auto X = [&](int l) { return EXT + (uint64_t)l * per_layer; };                 // input of layer l = output of l-1
+  auto KC = [&](int l) { return X(l) + up(xbytes); };
+  auto VC = [&](int l) { return KC(l) + up(cache_bytes); };
+  uint64_t boff[TS_NB_MOE], bbytes[TS_NB_MOE];
+  for (int i = 0; i < nb; ++i) {
+    size_t o, n;
+    int rc = ts_layer_boundary(&d, T, B, i, &o, &n);
+    if (rc != TS_OK) return rc;
+    boff[i] = o == (size_t)-1 ? 0 : WS + o;
+    bbytes[i] = n;
+  }
+  size_t moe_off[6] = {0, 0, 0, 0, 0, 0};
+  uint64_t moe_bytes[6] = {0, 0, 0, 0, 0, 0};
+  if (moe) {
+    int rc = ts_layer_moe_buffers(&d, T, B, moe_off);
+    if (rc != TS_OK) return rc;
+    moe_bytes[0] = (uint64_t)T * d.E * 4; moe_bytes[1] = (uint64_t)T * d.k * 4; moe_bytes[2] = (uint64_t)T * d.k * 4;
+    moe_bytes[3] = (uint64_t)d.E * 4; moe_bytes[4] = (uint64_t)(d.E + 1) * 4; moe_bytes[5] = (uint64_t)T * d.k * 4;
+  }
+  const uint64_t nqd = (uint64_t)d.nq * d.d, row = (uint64_t)d.d * 2;
+  out.reads.assign((size_t)n_layers * nb, {});
+  out.writes.assign((size_t)n_layers * nb, {});
+  const bool bb = which & kBoundaryBuffers, st = which & kSideTables;
+  auto full = [](uint64_t a, uint64_t n) { return ts_access{a, n, n, 0}; };
+  for (int l = 0; l < n_layers; ++l) {
+    auto R = [&](int node) -> std::vector<ts_access>& { return out.reads[(size_t)l * nb + node]; };
+    auto W = [&](int node) -> std::vector<ts_access>& { return out.writes[(size_t)l * nb + node]; };
+    auto bnd = [&](int i) { return full(i == nb - 1 ? X(l + 1) : boff[i], bbytes[i]); };
+    if (bb) {
+      R(TS_B_H1).push_back(full(X(l), xbytes));
+      W(TS_B_H1).push_back(bnd(TS_B_H1));
+      R(TS_B_QKV).push_back(bnd(TS_B_H1));
+      W(TS_B_QKV).push_back(bnd(TS_B_QKV));
+      if (d.mode == TS_MODE_DECODE) {
+        for (int b = 0; b < B; ++b)
+          for (int h = 0; h < d.nkv; ++h) {
+            const uint64_t o = (((uint64_t)b * d.nkv + h) * d.Lcap + (uint64_t)(kv_len - 1)) * row;
+            W(TS_B_QKV).push_back(ts_access{KC(l) + o, row, row, (int64_t)row});
+            W(TS_B_QKV).push_back(ts_access{VC(l) + o, row, row, (int64_t)row});
+          }
+        R(TS_B_ATTN).push_back(ts_access{boff[TS_B_QKV], bbytes[TS_B_QKV], (uint64_t)T * nqd * 2, 0});
+        const uint64_t kv_read = (uint64_t)B * d.nkv * kv_len * row;
+        R(TS_B_ATTN).push_back(ts_access{KC(l), cache_bytes, kv_read, 0});
+        R(TS_B_ATTN).push_back(ts_access{VC(l), cache_bytes, kv_read, 0});
+      } else {
+        const uint64_t kv_new = (uint64_t)T * d.nkv * row;
+        W(TS_B_QKV).push_back(ts_access{KC(l), cache_bytes, std::min(kv_new, cache_bytes), 0});
+        W(TS_B_QKV).push_back(ts_access{VC(l), cache_bytes, std::min(kv_new, cache_bytes), 0});
+        R(TS_B_ATTN).push_back(bnd(TS_B_QKV));
+      }
+      W(TS_B_ATTN).push_back(bnd(TS_B_ATTN));
+      R(TS_B_X2).push_back(bnd(TS_B_ATTN));
+      R(TS_B_X2).push_back(full(X(l), xbytes));
+      W(TS_B_X2).push_back(bnd(TS_B_X2));
+      R(TS_B_H2).push_back(bnd(TS_B_X2));
+      W(TS_B_H2).push_back(bnd(TS_B_H2));
+      R(TS_B_GATE_UP).push_back(bnd(TS_B_H2));
+      W(TS_B_GATE_UP).push_back(bnd(TS_B_GATE_UP));
+      R(TS_B_ACT).push_back(bnd(TS_B_GATE_UP));
+      W(TS_B_ACT).push_back(bnd(TS_B_ACT));
+      if (!moe) {
+        R(TS_B_OUT_DENSE).push_back(bnd(TS_B_ACT));
+        R(TS_B_OUT_DENSE).push_back(bnd(TS_B_X2));
+        W(TS_B_OUT_DENSE).push_back(bnd(TS_B_OUT_DENSE));
+      } else {
+        R(TS_B_Y_MOE).push_back(bnd(TS_B_ACT));
+        W(TS_B_Y_MOE).push_back(bnd(TS_B_Y_MOE));
+        R(TS_B_OUT_MOE).push_back(bnd(TS_B_Y_MOE));
+        R(TS_B_OUT_MOE).push_back(bnd(TS_B_X2));
+        W(TS_B_OUT_MOE).push_back(bnd(TS_B_OUT_MOE));
+      }
+    }
+    if (st && moe) {
+      for (int i = 0; i < 6; ++i) W(TS_B_GATE_UP).push_back(full(WS + moe_off[i], moe_bytes[i]));
+      R(TS_B_Y_MOE).push_back(full(WS + moe_off[4], moe_bytes[4]));     // expert offsets
+      R(TS_B_OUT_MOE).push_back(full(WS + moe_off[5], moe_bytes[5]));   // permutation
+      R(TS_B_OUT_MOE).push_back(full(WS + moe_off[2], moe_bytes[2]));   // routing weights
+    }
+  }
+  out.io.resize(out.reads.size());
+  for (size_t i = 0; i < out.io.size(); ++i)
+    out.io[i] = ts_kernel_io{out.reads[i].data(), out.writes[i].data(), (int32_t)out.reads[i].size(),
+                             (int32_t)out.writes[i].size()};
+  return TS_OK;
+}
+
+int check_layer_args(const ts_layer_desc* desc, int T, int B, int kv_len, const char* who) {
+  TS_REQUIRE(desc != nullptr, TS_ERR_INVALID_ARG, "%s: null desc", who);
+  TS_REQUIRE(T >= 1 && B >= 1, TS_ERR_INVALID_ARG, "%s: T=%d B=%d must be positive", who, T, B);
+  if (desc->mode == TS_MODE_DECODE) {
+    TS_REQUIRE(T == B, TS_ERR_INVALID_ARG, "%s: a decode step has one token per sequence (T=%d, B=%d)", who, T, B);
+    TS_REQUIRE(kv_len >= 1 && kv_len < desc->Lcap, TS_ERR_INVALID_ARG,
+               "%s: kv_len=%d must leave room for the next position (Lcap=%d)", who, kv_len, desc->Lcap);
+  }
+  return TS_OK;
+}
+
+}  // namespace
+}  // namespace ts
+
+using namespace ts;
+
+extern "C" {
+
+int ts_ddg_build(const ts_kernel_io* kernels, int n_kernels, ts_ddg_edge* edges, int max_edges, int* n_edges) {
+  TS_REQUIRE(n_kernels >= 0 && (kernels != nullptr || n_kernels == 0) && n_edges != nullptr && max_edges >= 0 &&
+                 (edges != nullptr || max_edges == 0),
+             TS_ERR_INVALID_ARG, "ts_ddg_build: null or negative argument");
+  for (int k = 0; k < n_kernels; ++k)
+    TS_REQUIRE(kernels[k].n_reads >= 0 && kernels[k].n_writes >= 0 && (kernels[k].reads || kernels[k].n_reads == 0) &&
+                   (kernels[k].writes || kernels[k].n_writes == 0),
+               TS_ERR_INVALID_ARG, "ts_ddg_build: kernel %d has a null access list", k);
+  std::vector<ts_ddg_edge> out;
+  ddg_build_impl(kernels, n_kernels, out);
+  *n_edges = (int)out.size();
+  TS_REQUIRE((int)out.size() <= max_edges, TS_ERR_WORKSPACE, "ts_ddg_build: %zu edges, room for %d", out.size(), max_edges);
+  std::copy(out.begin(), out.end(), edges);
+  return TS_OK;
+}
+
+int ts_layer_ddg(const ts_layer_desc* desc, int T, int B, int kv_len, int n_layers, ts_ddg_edge* edges, int max_edges,
+                 int* n_edges) {
+  int rc = check_layer_args(desc, T, B, kv_len, "ts_layer_ddg");
+  if (rc != TS_OK) return rc;
+  TS_REQUIRE(n_layers >= 1 && n_layers <= 4096 && n_edges != nullptr, TS_ERR_INVALID_ARG, "ts_layer_ddg: bad n_layers %d", n_layers);
+  LayerNodes nodes;
+  rc = build_layer_nodes(*desc, T, B, kv_len, n_layers, kBoundaryBuffers | kSideTables, nodes);
+  if (rc != TS_OK) return rc;
+  return ts_ddg_build(nodes.io.data(), (int)nodes.io.size(), edges, max_edges, n_edges);
+}
+
+const char* ts_layer_node_name(const ts_layer_desc* desc, int node) {
+  static const char* dense[TS_NB_DENSE] = {"rmsnorm1", "qkv_rope_append", "attention", "o_proj_residual",
+                                           "rmsnorm2", "gate_up", "swiglu", "down_residual"};
+  static const char* moe[TS_NB_MOE] = {"rmsnorm1", "qkv_rope_append", "attention", "o_proj_residual", "rmsnorm2",
+                                       "route_expert_gate_up", "swiglu", "expert_down", "combine_residual"};
+  if (desc == nullptr || node < 0) return nullptr;
+  if (desc->E > 0) return node < TS_NB_MOE ? moe[node] : nullptr;
+  return node < TS_NB_DENSE ? dense[node] : nullptr;
+}
+
+int ts_layer_cut_mask(const ts_layer_desc* desc, const int32_t* placement, uint64_t* boundary_mask) {
+  TS_REQUIRE(desc != nullptr && placement != nullptr && boundary_mask != nullptr, TS_ERR_INVALID_ARG,
+             "ts_layer_cut_mask: null argument");
+  ts_layer_desc d = *desc;
+  d.mode = TS_MODE_PREFILL;               // the graph's topology does not depend on the mode or the sizes
+  const int nb = d.E > 0 ? TS_NB_MOE : TS_NB_DENSE;
+  uint64_t mask = 0;
+  for (int which : {kBoundaryBuffers, kSideTables}) {
+    LayerNodes nodes;
+    int rc = build_layer_nodes(d, 1, 1, 1, 1, which, nodes);
+    if (rc != TS_OK) return rc;
+    std::vector<ts_ddg_edge> edges;
+    ddg_build_impl(nodes.io.data(), nb, edges);
+    for (const ts_ddg_edge& e : edges) {
+      if (e.cross_iteration || placement[e.src] == placement[e.dst]) continue;
+      TS_REQUIRE(which == kBoundaryBuffers, TS_ERR_UNSUPPORTED_SHAPE,
+                 "ts_layer_cut_mask: nodes %d and %d exchange routing tables and must share a GPU", e.src, e.dst);
+      mask |= 1ull << e.src;
+    }
+  }
+  if (placement[nb - 1] != placement[nb]) mask |= 1ull << (nb - 1);
+  *boundary_mask = mask;
+  return TS_OK;
+}
+
+int ts_plan_policy(const ts_plan_problem* pr, int objective, int64_t node_limit, int32_t* placement, double* value,
+                   double* T_g, double* M_g, int* proved_optimal) {
+  TS_REQUIRE(pr != nullptr && placement != nullptr && value != nullptr, TS_ERR_INVALID_ARG, "ts_plan_policy: null argument");
+  TS_REQUIRE(pr->n_kernels >= 1 && pr->n_gpus >= 1 && pr->n_gpus <= 64 && pr->n_edges >= 0, TS_ERR_INVALID_ARG,
+             "ts_plan_policy: bad sizes (kernels %d, gpus %d, edges %d)", pr->n_kernels, pr->n_gpus, pr->n_edges);
+  TS_REQUIRE(pr->t != nullptr && (pr->n_edges == 0 || pr->edges != nullptr) && (pr->n_gpus == 1 || (pr->bw && pr->lat)),
+             TS_ERR_INVALID_ARG, "ts_plan_policy: null table");
+  TS_REQUIRE(objective == TS_PLAN_THROUGHPUT || objective == TS_PLAN_LATENCY, TS_ERR_INVALID_ARG,
+             "ts_plan_policy: unknown objective %d", objective);
+  Problem p;
+  p.K = pr->n_kernels;
+  p.G = pr->n_gpus;
+  p.t = pr->t;
+  p.bw = pr->bw;
+  p.lat = pr->lat;
+  p.in.resize(p.K);
+  for (int e = 0; e < pr->n_edges; ++e) {
+    const ts_ddg_edge& ed = pr->edges[e];
+    if (ed.cross_iteration) continue;                      // replicated buffers: no cost in the objectives
+    TS_REQUIRE(ed.src >= 0 && ed.src < ed.dst && ed.dst < p.K, TS_ERR_INVALID_ARG,
+               "ts_plan_policy: edge %d (%d -> %d) does not follow execution order", e, ed.src, ed.dst);
+    p.in[ed.dst].push_back({ed.src, (double)ed.bytes});
+  }
+  for (int i = 0; i < p.K * p.G; ++i)
+    TS_REQUIRE(pr->t[i] >= 0.0 && std::isfinite(pr->t[i]), TS_ERR_INVALID_ARG, "ts_plan_policy: negative or non-finite latency");
+
+  std::vector<int32_t> best_place;
+  double best = 0.0;
+  bool optimal = true;
+  if (!(objective == TS_PLAN_LATENCY && plan_latency_dp(p, best_place, best))) {
+    BnB s{p, objective, node_limit > 0 ? node_limit : (int64_t)50'000'000};
+    s.T.assign(p.G, 0.0);
+    s.M.assign(p.G, 0.0);
+    s.place.assign(p.K, 0);
+    s.rem_min.assign(p.K + 1, 0.0);
+    for (int k = p.K - 1; k >= 0; --k) {
+      double mn = p.t[k * p.G];
+      for (int g = 1; g < p.G; ++g) mn = std::min(mn, p.t[k * p.G + g]);
+      s.rem_min[k] = s.rem_min[k + 1] + mn;
+    }
+    // incumbent: the best single GPU (always feasible, no communication)
+    for (int g = 0; g < p.G; ++g) {
+      double v = 0.0;
+      for (int k = 0; k < p.K; ++k) v += p.t[k * p.G + g];
+      if (v < s.best) { s.best = v; s.best_place.assign(p.K, g); }
+    }
+    if (p.G > 1 && p.K <= 4096) {
+      std::vector<int32_t> seed;
+      std::vector<double> T, M;
+      contiguous_seed(p, seed);
+      evaluate(p, seed.data(), T, M);
+      s.T = T; s.M = M;
+      const double v = s.bound(p.K);                     // with every kernel placed the bound is the objective
+      if (v < s.best) { s.best = v; s.best_place = seed; }
+      s.T.assign(p.G, 0.0);
+      s.M.assign(p.G, 0.0);
+    }
+    s.dfs(0);
+    best_place = s.best_place;
+    optimal = !s.exhausted;
+  }
+  std::vector<double> T, M;
+  evaluate(p, best_place.data(), T, M);
+  double v = 0.0;
+  if (objective == TS_PLAN_THROUGHPUT) {
+    for (int g = 0; g < p.G; ++g) v = std::max(v, std::max(T[g], M[g]));
+  } else {
+    for (int g = 0; g < p.G; ++g) v += T[g];
+    for (int g = 0; g < p.G; ++g) v += M[g];
+  }
+  std::copy(best_place.begin(), best_place.end(), placement);
+  *value = v;
+  if (T_g) std::copy(T.begin(), T.end(), T_g);
+  if (M_g) std::copy(M.begin(), M.end(), M_g);
+  if (proved_optimal) *proved_optimal = optimal ? 1 : 0;
+  return TS_OK;
+}
+
+}  // extern "C"

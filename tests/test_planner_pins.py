@@ -78,6 +78,20 @@ def test_ddg_cross_iteration_cache():
     assert cross == {(1, 0): 16}
 
 
+def test_ddg_append_position_advances_between_iterations():
+    # two cache rows of 10 slots x 4 bytes; k0 appends one slot per row (slot 3 now, slot 4 next iteration),
+    # k1 reads both rows whole.  Inside the iteration 2 x 4 new bytes flow; the slots appended by the previous
+    # iteration are still the latest content of their bytes, so 2 x 4 bytes arrive across the iteration boundary.
+    rows = [0, 40]
+    ks = [K(writes=[(r + 3 * 4, 4, 4, 4) for r in rows]), K(reads=[(0, 80, 80)])]
+    edges, cross = P.ddg_build(ks)
+    assert edges == {(0, 1): 8}
+    assert cross == {(0, 1): 8}
+    # without the advance the second iteration overwrites the same slots: nothing crosses
+    ks = [K(writes=[(r + 3 * 4, 4, 4) for r in rows]), K(reads=[(0, 80, 80)])]
+    assert P.ddg_build(ks) == ({(0, 1): 8}, {})
+
+
 def test_ddg_flow_is_bounded_by_both_sides():
     rng = np.random.default_rng(5)
     for _ in range(50):
