@@ -381,6 +381,32 @@ typedef struct ts_plan_problem {
 int ts_plan_policy(const ts_plan_problem* problem, int objective, int64_t node_limit,
                    int32_t* placement, double* value, double* T_g, double* M_g,
                    int* proved_optimal);
+
+/* ---------------------------------------------------------------------------
+ * Online monitor (Sec. 3.4).  HOST-only, O(1) state, not thread-safe.
+ * Time is cut into windows [n W, (n+1) W).  ts_monitor_record reports one
+ * finished request: its completion time (seconds on any monotonic clock that
+ * starts at 0), its end-to-end latency, the latency of each of its kernel
+ * groups (the kernels between two consecutive communication operations) and
+ * its communication time; execution latency = sum of the groups + comm.
+ * Completion times may arrive in any order inside the open window but never
+ * in a window that has already closed (TS_ERR_INVALID_ARG).
+ * When a window closes with at least one completion, ratio = (mean request
+ * latency) / (mean execution latency); ratio > beta selects
+ * TS_PLAN_THROUGHPUT, otherwise TS_PLAN_LATENCY.  Empty windows keep the policy.
+ * ts_monitor_advance closes every window that ended at or before now_s and
+ * reports the policy in effect, the number of windows closed and of policy
+ * switches so far, and the ratio of the last non-empty window (NaN before the
+ * first); any of the four outputs may be NULL.  The paper's defaults are
+ * window_s = 0.3 and beta = 1.5 (Sec. 5.4).
+ */
+typedef struct ts_monitor ts_monitor;
+int ts_monitor_create(double window_s, double beta, int initial_policy, ts_monitor** out);
+void ts_monitor_destroy(ts_monitor* m);
+int ts_monitor_record(ts_monitor* m, double t_complete_s, double request_latency_s,
+                      const double* group_latency_s, int n_groups, double comm_s);
+int ts_monitor_advance(ts_monitor* m, double now_s, int* policy, int64_t* windows_closed,
+                       int64_t* n_switches, double* last_ratio);
 #if defined(__GNUC__)
 #pragma GCC visibility pop
 #endif

@@ -27,6 +27,7 @@ EXPORTS = [
     "ts_layer_workspace_bytes", "ts_layer_boundary", "ts_layer_moe_buffers", "ts_layer_forward",
     "ts_pipeline_create", "ts_pipeline_destroy", "ts_pipeline_boundary_layout", "ts_pipeline_slot_stride",
     "ts_pipeline_step", "ts_ddg_build", "ts_layer_ddg", "ts_layer_node_name", "ts_layer_cut_mask", "ts_plan_policy",
+    "ts_monitor_create", "ts_monitor_destroy", "ts_monitor_record", "ts_monitor_advance",
 ]
 
 
@@ -87,6 +88,7 @@ def _load() -> C.CDLL:
         getattr(lib, n).restype = C.c_size_t
     lib.ts_pipeline_destroy.restype = None
     lib.ts_layer_node_name.restype = C.c_char_p
+    lib.ts_monitor_destroy.restype = None
     return lib
 
 
@@ -125,6 +127,11 @@ lib.ts_layer_node_name.argtypes = [C.POINTER(LayerDesc), _i]
 lib.ts_layer_cut_mask.argtypes = [C.POINTER(LayerDesc), C.POINTER(C.c_int32), C.POINTER(_u64)]
 lib.ts_plan_policy.argtypes = [C.POINTER(PlanProblem), _i, C.c_int64, C.POINTER(C.c_int32), C.POINTER(C.c_double),
                                C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(_i)]
+lib.ts_monitor_create.argtypes = [C.c_double, C.c_double, _i, C.POINTER(_p)]
+lib.ts_monitor_destroy.argtypes = [_p]
+lib.ts_monitor_record.argtypes = [_p, C.c_double, C.c_double, C.POINTER(C.c_double), _i, C.c_double]
+lib.ts_monitor_advance.argtypes = [_p, C.c_double, C.POINTER(_i), C.POINTER(C.c_int64), C.POINTER(C.c_int64),
+                                   C.POINTER(C.c_double)]
 
 
 def _ptr(t) -> Optional[int]:
@@ -362,6 +369,29 @@ def ts_plan_policy(t, edges, bw, lat, objective: int, node_limit: int = 0):
     Tg, Mg = (C.c_double * G)(), (C.c_double * G)()
     _check(lib.ts_plan_policy(C.byref(prob), objective, node_limit, place, C.byref(val), Tg, Mg, C.byref(opt)))
     return list(place), val.value, list(Tg), list(Mg), bool(opt.value)
+
+
+def ts_monitor_create(window_s: float = 0.3, beta: float = 1.5, initial_policy: int = TS_PLAN_LATENCY) -> int:
+    h = _p()
+    _check(lib.ts_monitor_create(window_s, beta, initial_policy, C.byref(h)))
+    return h.value
+
+
+def ts_monitor_destroy(handle: int) -> None:
+    lib.ts_monitor_destroy(handle)
+
+
+def ts_monitor_record(handle: int, t_complete: float, request_latency: float, group_latencies: Sequence[float],
+                      comm: float) -> None:
+    arr = (C.c_double * max(1, len(group_latencies)))(*group_latencies)
+    _check(lib.ts_monitor_record(handle, t_complete, request_latency, arr, len(group_latencies), comm))
+
+
+def ts_monitor_advance(handle: int, now: float):
+    """Returns (policy, windows closed, switches, ratio of the last non-empty window)."""
+    pol, nwin, nsw, ratio = _i(), C.c_int64(), C.c_int64(), C.c_double()
+    _check(lib.ts_monitor_advance(handle, now, C.byref(pol), C.byref(nwin), C.byref(nsw), C.byref(ratio)))
+    return pol.value, nwin.value, nsw.value, ratio.value
 
 
 class KernelProfile:

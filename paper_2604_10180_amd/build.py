@@ -9,7 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libtessera.so")
-SOURCES = ["elementwise.hip", "moe.hip", "gemm.hip", "gemm_mfma.hip", "attention_decode.hip", "attention_prefill.hip", "api.hip", "planner.hip"]
+SOURCES = ["elementwise.hip", "moe.hip", "gemm.hip", "gemm_mfma.hip", "attention_decode.hip", "attention_prefill.hip", "api.hip", "planner.hip", "monitor.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-fvisibility=hidden",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
