@@ -98,6 +98,55 @@ FAMILY_OF_LAUNCH = {
 }
 
 
+NODE_OF_STEP = {"rmsnorm1": 0, "qkv": 1, "rope+append": 1, "attention": 2, "o": 3, "rmsnorm2": 4, "gate_up": 5, "swiglu": 6,
+                "down": 7, "router": 5, "route": 5, "expert gate_up": 5, "expert down": 7, "combine": 8}
+# Second GPU types of the planner demonstration: dense bf16 TFLOP/s and HBM GB/s as the paper's Table 1 lists them.
+MODELLED_GPUS = {"L40S-like": (366.5, 864.0), "H100-like": (989.0, 3350.0)}
+
+
+def plan_section(B, wl, desc, kernels, n_layers=4, link_GBps=25.0, link_latency_s=5e-6):
+    """Policy planner (Sec. 3.2) on measured kernel-group times: GPU 0 is this MI355X (times measured above,
+    launches grouped by the layer node they belong to), GPU 1 a modelled device whose time for a node is the
+    measured time scaled by the ratio of the two devices' roofline times for that node's bytes and flops.
+    The link is the 200 Gbps NIC of the paper's testbed.  Nothing is executed on a second GPU."""
+    nb = B.TS_NB_MOE if wl.shape.E > 0 else B.TS_NB_DENSE
+    t0, nbytes, flops, node = [0.0] * nb, [0.0] * nb, [0.0] * nb, 0
+    for k in kernels:
+        if "step" in k:
+            node = NODE_OF_STEP[k["step"]]
+            nbytes[node] += k["algo_bytes"]
+            flops[node] += k.get("TFLOPs", 0.0) * 1e12 * k["avg_us"] * 1e-6
+        t0[node] += k["avg_us"] * 1e-6
+    kv_len = int(wl.ctx) if (wl.mode == "decode" and wl.ctx) else 1024
+    kv_len = min(kv_len, desc.Lcap - 1)
+    edges = B.ts_layer_ddg(desc, wl.T, wl.B, kv_len, n_layers)
+    names = [B.ts_layer_node_name(desc, i) for i in range(nb)]
+    out = {"n_layers": n_layers, "nodes": names, "t_mi355x_us": [round(v * 1e6, 2) for v in t0],
+           "link": {"GBps": link_GBps, "latency_us": link_latency_s * 1e6}, "edges_per_layer": len(edges) // n_layers}
+    roof = lambda i, tf, gb: max(flops[i] / (tf * 1e12), nbytes[i] / (gb * 1e9))
+    for gname, (tf, gb) in MODELLED_GPUS.items():
+        t1 = [t0[i] * roof(i, tf, gb) / roof(i, MFMA_BF16_PEAK_TFLOPS, HBM_PEAK_GBS) for i in range(nb)]
+        t = [[t0[k % nb], t1[k % nb]] for k in range(nb * n_layers)]
+        bw = [[float("inf"), link_GBps * 1e9], [link_GBps * 1e9, float("inf")]]
+        lat = [[0.0, link_latency_s], [link_latency_s, 0.0]]
+        entry = {"t_modelled_us": [round(v * 1e6, 2) for v in t1]}
+        for oname, obj in (("throughput", B.TS_PLAN_THROUGHPUT), ("latency", B.TS_PLAN_LATENCY)):
+            tic = time.perf_counter()
+            place, val, Tg, Mg, opt = B.ts_plan_policy(t, edges, bw, lat, obj, node_limit=2_000_000)
+            solve_ms = (time.perf_counter() - tic) * 1e3
+            first = place[:nb] + [place[nb] if n_layers > 1 else place[nb - 1]]
+            try:
+                mask = B.ts_layer_cut_mask(desc, first)
+            except B.TesseraError:
+                mask = None
+            entry[oname] = {"value_us": round(val * 1e6, 2), "mi355x_alone_us": round(sum(t0) * n_layers * 1e6, 2),
+                            "T_g_us": [round(v * 1e6, 2) for v in Tg], "M_g_us": [round(v * 1e6, 2) for v in Mg],
+                            "placement_layer0": place[:nb], "on_modelled_gpu": int(sum(place)),
+                            "boundary_mask_layer0": mask, "proved_optimal": opt, "solve_ms": round(solve_ms, 2)}
+        out[gname] = entry
+    return out
+
+
 def time_pipeline(B, torch, wl, desc, dev_set, io_cpu, dev, steps, warmup):
     """ts_pipeline_step over wl.n_micro micro-batches (index order), three ways: no boundary
     copies, all boundaries copied on the side stream, all boundaries copied on the compute
@@ -154,6 +203,8 @@ def main():
     ap.add_argument("--pipeline", action="store_true",
                     help="also time ts_pipeline_step over the workload's micro-batches: boundary copies off, "
                          "on the side stream, and serialised on the compute streams")
+    ap.add_argument("--plan", action="store_true",
+                    help="also run the policy planner on the measured kernel-group times against modelled second GPUs")
     ap.add_argument("--calibration-copy", action="store_true",
                     help="also run one 256 MiB elementwise copy (known traffic; used to scale rocprofv3 --pmc counters)")
     args = ap.parse_args()
@@ -269,6 +320,9 @@ def main():
 
     if args.pipeline and wl.mode == "decode" and wl.n_micro > 1:
         result["pipeline"] = time_pipeline(B, torch, wl, desc, sets[0], io, dev, max(5, args.steps // 2), args.warmup)
+
+    if args.plan:
+        result["plan"] = plan_section(B, wl, desc, kernels)
 
     if not args.no_cpu_baseline:
         from oracle import decoder_layer as O

@@ -255,8 +255,28 @@ struct BnB {
       mx = std::max(mx, std::max(T[g], M[g]));
       sum += T[g];
     }
-    return std::max(mx, sum / p.G);
+    mx = std::max(mx, sum / p.G);
+    if (p.G == 2 && k < p.K) mx = std::max(mx, two_gpu_fractional(k));
+    return mx;
   }
+  // Two GPUs: the makespan when the remaining kernels may be split fractionally between the two (no
+  // communication) bounds every integral completion from below.  Start with all of them on GPU 0 and move
+  // them over in ascending order of (time on GPU 1) / (time on GPU 0) until the two loads meet.
+  std::vector<int> by_ratio;                   // all kernels, ascending t[k][1] / t[k][0]
+  double two_gpu_fractional(int k) const {
+    double L0 = T[0] + rem0[k], L1 = T[1];
+    if (L1 >= L0) return L1;
+    for (int j : by_ratio) {
+      if (j < k) continue;
+      const double a = p.t[j * 2], b = p.t[j * 2 + 1];
+      if (a <= 0.0) break;                     // nothing left that relieves GPU 0
+      if (L1 + b <= L0 - a) { L0 -= a; L1 += b; continue; }
+      const double y = (L0 - L1) / (a + b);    // fraction of kernel j that makes the loads equal
+      return L1 + y * b;
+    }
+    return std::max(L0, L1);
+  }
+  std::vector<double> rem0;                    // rem0[k] = sum_{j >= k} t[j][0]
   void dfs(int k) {
     if (exhausted) return;
     if (++nodes > node_limit) { exhausted = true; return; }
@@ -519,6 +539,16 @@ int ts_plan_policy(const ts_plan_problem* pr, int objective, int64_t node_limit,
       double mn = p.t[k * p.G];
       for (int g = 1; g < p.G; ++g) mn = std::min(mn, p.t[k * p.G + g]);
       s.rem_min[k] = s.rem_min[k + 1] + mn;
+    }
+    if (p.G == 2) {
+      s.rem0.assign(p.K + 1, 0.0);
+      for (int k = p.K - 1; k >= 0; --k) s.rem0[k] = s.rem0[k + 1] + p.t[k * 2];
+      s.by_ratio.resize(p.K);
+      for (int k = 0; k < p.K; ++k) s.by_ratio[k] = k;
+      auto ratio = [&](int x) {
+        return p.t[x * 2] > 0.0 ? p.t[x * 2 + 1] / p.t[x * 2] : std::numeric_limits<double>::infinity();
+      };
+      std::stable_sort(s.by_ratio.begin(), s.by_ratio.end(), [&](int x, int y) { return ratio(x) < ratio(y); });
     }
     // incumbent: the best single GPU (always feasible, no communication)
     for (int g = 0; g < p.G; ++g) {
