@@ -91,7 +91,7 @@ def measured_traffic(workload, launch, step):
 
 
 FAMILY_OF_LAUNCH = {
-    "rmsnorm": "rmsnorm", "rmsnorm_splitk": "rmsnorm", "rope_splitk": "rope", "gemm_skinny": "gemm", "gemm_tiled": "gemm", "gemm_mfma256": "gemm", "splitk_reduce": None, "rope": "rope",
+    "rmsnorm": "rmsnorm", "gemm_skinny": "gemm", "gemm_tiled": "gemm", "gemm_mfma256": "gemm", "splitk_reduce": None, "rope": "rope",
     "attn_decode_split": "attn_decode", "attn_decode_merge": None, "attn_prefill": "attn_prefill",
     "swiglu": "swiglu", "moe_topk": "moe_route", "moe_group": None, "moe_invert": None, "moe_combine": "moe_combine",
     "copy16": None,

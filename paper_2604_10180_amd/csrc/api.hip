@@ -202,17 +202,10 @@ int layer_forward_impl(const ts_layer_desc& d, const ts_layer_weights& w, const 
 #define TS_STEP(call) do { rc = (call); if (rc != TS_OK) return rc; } while (0)
   TS_STEP(launch_rmsnorm(io.x, w.gamma1, h1, T, d.H, d.eps, s, counters, p.counter_words));
   TS_STEP(hook(TS_B_H1, h1));
-  // A projection that was split along K leaves its slices in the scratch area and the next kernel adds them
-  // up while it reads them (same arithmetic and rounding as the stand-alone reduce): one launch less.
-  SplitKPartial sk;
-  TS_STEP(launch_gemm(h1, w.w_qkv, nullptr, qkv, false, T, nqkv, d.H, scratch, p.scratch_bytes, s, &sk));
-  if (sk.S > 1)
-    TS_STEP(launch_rope_splitk(sk, qkv, io.pos, io.seq_id, w.rope_cos_sin, w.rope_cos_sin ? w.rope_table_len : 0,
-                               io.kcache, io.vcache, T, d.nq, d.nkv, d.d, d.Lcap, d.rope_base, s));
-  else
-    TS_STEP(launch_rope(qkv, qkv + nqd, qkv + nqd + nkd, nqkv, nqkv, io.pos, io.seq_id, w.rope_cos_sin,
-                        w.rope_cos_sin ? w.rope_table_len : 0, io.kcache, io.vcache, T, d.nq, d.nkv, d.d, d.Lcap,
-                        d.rope_base, s));
+  TS_STEP(launch_gemm(h1, w.w_qkv, nullptr, qkv, false, T, nqkv, d.H, scratch, p.scratch_bytes, s));
+  TS_STEP(launch_rope(qkv, qkv + nqd, qkv + nqd + nkd, nqkv, nqkv, io.pos, io.seq_id, w.rope_cos_sin,
+                      w.rope_cos_sin ? w.rope_table_len : 0, io.kcache, io.vcache, T, d.nq, d.nkv, d.d, d.Lcap,
+                      d.rope_base, s));
   TS_STEP(hook(TS_B_QKV, qkv));
   if (d.mode == TS_MODE_DECODE) {
     TS_STEP(launch_attention_decode(qkv, nqkv, io.kcache, io.vcache, io.seq_lens, attn, B, d.nq, d.nkv, d.d, d.Lcap,
@@ -222,14 +215,9 @@ int layer_forward_impl(const ts_layer_desc& d, const ts_layer_weights& w, const 
                                      io.max_seqlen, d.nq, d.nkv, d.d, scale, 1, s));
   }
   TS_STEP(hook(TS_B_ATTN, attn));
-  TS_STEP(launch_gemm(attn, w.w_o, io.x, x2, false, T, d.H, nqd, scratch, p.scratch_bytes, s, &sk));
-  if (sk.S > 1) {
-    TS_STEP(launch_rmsnorm_splitk(sk, io.x, x2, w.gamma2, h2, T, d.H, d.eps, s));
-    TS_STEP(hook(TS_B_X2, x2));
-  } else {
-    TS_STEP(hook(TS_B_X2, x2));
-    TS_STEP(launch_rmsnorm(x2, w.gamma2, h2, T, d.H, d.eps, s));
-  }
+  TS_STEP(launch_gemm(attn, w.w_o, io.x, x2, false, T, d.H, nqd, scratch, p.scratch_bytes, s));
+  TS_STEP(hook(TS_B_X2, x2));
+  TS_STEP(launch_rmsnorm(x2, w.gamma2, h2, T, d.H, d.eps, s));
   TS_STEP(hook(TS_B_H2, h2));
   if (d.E == 0) {
     TS_STEP(launch_gemm(h2, w.w_gate_up, nullptr, gate_up, false, T, 2 * d.F, d.H, scratch, p.scratch_bytes, s));

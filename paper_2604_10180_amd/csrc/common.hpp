@@ -118,35 +118,17 @@ __device__ __forceinline__ float wave_max(float v) {
 // ---- internal launchers (host), one per kernel family -----------------------
 // `zero`/`nzero`: optional int32 words the kernel clears on the side (the layer uses this to arm
 // the arrival counters of the kernels that follow on the same stream).
-// fp32 partial products of a projection that was split along K and whose slices have not been added yet:
-// partial[s][m][n], s < S.  The consumer adds them in ascending s, adds the residual if the projection has
-// one, and rounds once to bf16: the same arithmetic as the stand-alone reduce kernel.
-struct SplitKPartial {
-  const float* partial = nullptr;
-  int S = 1;
-};
 int launch_rmsnorm(const ts_bf16* x, const ts_bf16* gamma, ts_bf16* y, int T, int H, float eps, hipStream_t s,
                    int32_t* zero = nullptr, int nzero = 0);
-// x = sum of the split-K slices + residual, written as bf16; y = RMSNorm(x) * gamma: the reduce of the
-// producing projection and the norm in one launch.
-int launch_rmsnorm_splitk(const SplitKPartial& in, const ts_bf16* residual, ts_bf16* x, const ts_bf16* gamma,
-                          ts_bf16* y, int T, int H, float eps, hipStream_t s);
 int launch_swiglu(const ts_bf16* gu, ts_bf16* out, int T, int F, hipStream_t s);
 int launch_rope(ts_bf16* q, ts_bf16* k, const ts_bf16* v, int q_stride, int kv_stride, const int32_t* pos,
                 const int32_t* seq_id, const float* cos_sin, int table_len, ts_bf16* kcache, ts_bf16* vcache,
                 int T, int nq, int nkv, int d, int Lcap, float base, hipStream_t s);
-// RoPE + cache append that first adds the split-K slices of the QKV projection; qkv is the packed
-// [T, (nq + 2 nkv) d] output buffer, written in full (q and k rotated, v as is).
-int launch_rope_splitk(const SplitKPartial& in, ts_bf16* qkv, const int32_t* pos, const int32_t* seq_id,
-                       const float* cos_sin, int table_len, ts_bf16* kcache, ts_bf16* vcache, int T, int nq, int nkv,
-                       int d, int Lcap, float base, hipStream_t s);
 int launch_copy16(const void* src, void* dst, size_t bytes, hipStream_t s, void* dst2 = nullptr);
 
 size_t gemm_workspace_bytes(int M, int N, int K);
-// defer != nullptr: when the projection is split along K the reduce launch is left out and *defer describes
-// the slices (in ws) for the consumer; defer->S == 1 means C has been written as usual.
 int launch_gemm(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, void* C, bool f32out, int M, int N,
-                int K, void* ws, size_t ws_bytes, hipStream_t s, SplitKPartial* defer = nullptr);
+                int K, void* ws, size_t ws_bytes, hipStream_t s);
 bool gemm_mfma256_supported(int M, int N, int K);
 int launch_gemm_mfma256(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, ts_bf16* C, int M, int N, int K,
                         hipStream_t s);

@@ -7,14 +7,10 @@ namespace ts {
 
 // ---------------------------------------------------------------- RMSNorm
 // One workgroup per row; the row stays in registers between the reduction and the scaling.
-// SPLITK: the row is first formed as sum of S fp32 slices (ascending) + residual, rounded to bf16 and
-// written to xout (what the stand-alone split-K reduce does); the norm then runs on the rounded row.
-template <int VPT, bool SPLITK>
+template <int VPT>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* __restrict__ x, const uint4* __restrict__ gamma,
                                                       uint4* __restrict__ y, int H8, float eps, float inv_h,
-                                                      int32_t* __restrict__ zero, int nzero,
-                                                      const float* __restrict__ partial, int S, long MN,
-                                                      uint4* __restrict__ xout) {
+                                                      int32_t* __restrict__ zero, int nzero) {
   const int row = blockIdx.x;
   const int tid = threadIdx.x;
   if (row == 0)
@@ -26,31 +22,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* __restrict__ 
   for (int i = 0; i < VPT; ++i) {
     int c = tid + i * 256;
     if (c < H8) {
-      if (SPLITK) {
-        float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        const float* pr = partial + ((size_t)row * H8 + c) * 8;
-#pragma unroll 8
-        for (int sl = 0; sl < S; ++sl) {
-          const float4 p0 = *reinterpret_cast<const float4*>(pr + (size_t)sl * MN);
-          const float4 p1 = *reinterpret_cast<const float4*>(pr + (size_t)sl * MN + 4);
-          a[0] += p0.x; a[1] += p0.y; a[2] += p0.z; a[3] += p0.w;
-          a[4] += p1.x; a[5] += p1.y; a[6] += p1.z; a[7] += p1.w;
-        }
-        if (x != nullptr) {
-          U4 r;
-          r.u = xr[c];
-#pragma unroll
-          for (int j = 0; j < 4; ++j) {
-            a[2 * j] += bf_lo(r.w[j]);
-            a[2 * j + 1] += bf_hi(r.w[j]);
-          }
-        }
-#pragma unroll
-        for (int j = 0; j < 4; ++j) v[i].w[j] = pack_bf16(a[2 * j], a[2 * j + 1]);
-        xout[(size_t)row * H8 + c] = v[i].u;
-      } else {
-        v[i].u = xr[c];
-      }
+      v[i].u = xr[c];
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         float a = bf_lo(v[i].w[j]), b = bf_hi(v[i].w[j]);
@@ -92,36 +64,12 @@ int launch_rmsnorm(const ts_bf16* x, const ts_bf16* gamma, ts_bf16* y, int T, in
   const uint4* gp = reinterpret_cast<const uint4*>(gamma);
   uint4* yp = reinterpret_cast<uint4*>(y);
   const float inv_h = 1.0f / (float)H;
-  const float* np = nullptr;
-  uint4* nx = nullptr;
-  if (vpt <= 1) TS_LAUNCH("rmsnorm", (rmsnorm_kernel<1, false>), grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero, np, 1, 0L, nx);
-  else if (vpt <= 2) TS_LAUNCH("rmsnorm", (rmsnorm_kernel<2, false>), grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero, np, 1, 0L, nx);
-  else if (vpt <= 4) TS_LAUNCH("rmsnorm", (rmsnorm_kernel<4, false>), grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero, np, 1, 0L, nx);
-  else if (vpt <= 8) TS_LAUNCH("rmsnorm", (rmsnorm_kernel<8, false>), grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero, np, 1, 0L, nx);
-  else TS_LAUNCH("rmsnorm", (rmsnorm_kernel<16, false>), grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero, np, 1, 0L, nx);
+  if (vpt <= 1) TS_LAUNCH("rmsnorm", rmsnorm_kernel<1>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero);
+  else if (vpt <= 2) TS_LAUNCH("rmsnorm", rmsnorm_kernel<2>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero);
+  else if (vpt <= 4) TS_LAUNCH("rmsnorm", rmsnorm_kernel<4>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero);
+  else if (vpt <= 8) TS_LAUNCH("rmsnorm", rmsnorm_kernel<8>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero);
+  else TS_LAUNCH("rmsnorm", rmsnorm_kernel<16>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero);
   TS_LAUNCH_CHECK("rmsnorm");
-  return TS_OK;
-}
-
-int launch_rmsnorm_splitk(const SplitKPartial& in, const ts_bf16* residual, ts_bf16* x, const ts_bf16* gamma, ts_bf16* y,
-                          int T, int H, float eps, hipStream_t s) {
-  if (T == 0) return TS_OK;
-  const int H8 = H / 8;
-  const int vpt = cdiv(H8, 256);
-  dim3 grid(T), block(256);
-  const uint4* rp = reinterpret_cast<const uint4*>(residual);
-  const uint4* gp = reinterpret_cast<const uint4*>(gamma);
-  uint4* yp = reinterpret_cast<uint4*>(y);
-  uint4* xo = reinterpret_cast<uint4*>(x);
-  const float inv_h = 1.0f / (float)H;
-  const long MN = (long)T * H;
-  int32_t* nz = nullptr;
-  if (vpt <= 1) TS_LAUNCH("rmsnorm_splitk", (rmsnorm_kernel<1, true>), grid, block, 0, s, rp, gp, yp, H8, eps, inv_h, nz, 0, in.partial, in.S, MN, xo);
-  else if (vpt <= 2) TS_LAUNCH("rmsnorm_splitk", (rmsnorm_kernel<2, true>), grid, block, 0, s, rp, gp, yp, H8, eps, inv_h, nz, 0, in.partial, in.S, MN, xo);
-  else if (vpt <= 4) TS_LAUNCH("rmsnorm_splitk", (rmsnorm_kernel<4, true>), grid, block, 0, s, rp, gp, yp, H8, eps, inv_h, nz, 0, in.partial, in.S, MN, xo);
-  else if (vpt <= 8) TS_LAUNCH("rmsnorm_splitk", (rmsnorm_kernel<8, true>), grid, block, 0, s, rp, gp, yp, H8, eps, inv_h, nz, 0, in.partial, in.S, MN, xo);
-  else TS_LAUNCH("rmsnorm_splitk", (rmsnorm_kernel<16, true>), grid, block, 0, s, rp, gp, yp, H8, eps, inv_h, nz, 0, in.partial, in.S, MN, xo);
-  TS_LAUNCH_CHECK("rmsnorm_splitk");
   return TS_OK;
 }
 
@@ -161,31 +109,12 @@ int launch_swiglu(const ts_bf16* gu, ts_bf16* out, int T, int F, hipStream_t s) 
 // Work item = (token, head, 8 consecutive pair indices): loads the lower-half and
 // upper-half 16-byte chunks of the head vector, rotates, stores; k items also write the
 // rotated row into the cache; v items copy their chunk into the cache.
-// SPLITK: q, k, v are the three column ranges of one packed [T, q_stride] buffer whose values still sit in
-// S fp32 slices (partial[s][t][col]); every 8-element chunk is first formed as the ascending sum of its
-// slices rounded to bf16 (the stand-alone split-K reduce), and the v chunks are written to the buffer too.
-template <bool SPLITK>
 __global__ __launch_bounds__(256) void rope_kernel(ts_bf16* __restrict__ q, ts_bf16* __restrict__ k,
                                                    const ts_bf16* __restrict__ v, int q_stride, int kv_stride,
                                                    const int32_t* __restrict__ pos, const int32_t* __restrict__ seq_id,
                                                    const float* __restrict__ cos_sin, int table_len,
                                                    ts_bf16* __restrict__ kcache, ts_bf16* __restrict__ vcache, int nq,
-                                                   int nkv, int d, int Lcap, float base,
-                                                   const float* __restrict__ partial, int S, long MN) {
-  // chunk of 8 values at column `col` of token t
-  auto load8 = [&](const ts_bf16* ptr, int t, int col) -> uint4 {
-    if (!SPLITK) return ldg16(ptr);
-    float a[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    const float* pr = partial + (size_t)t * q_stride + col;
-#pragma unroll 8
-    for (int sl = 0; sl < S; ++sl) {
-      const float4 p0 = *reinterpret_cast<const float4*>(pr + (size_t)sl * MN);
-      const float4 p1 = *reinterpret_cast<const float4*>(pr + (size_t)sl * MN + 4);
-      a[0] += p0.x; a[1] += p0.y; a[2] += p0.z; a[3] += p0.w;
-      a[4] += p1.x; a[5] += p1.y; a[6] += p1.z; a[7] += p1.w;
-    }
-    return make_uint4(pack_bf16(a[0], a[1]), pack_bf16(a[2], a[3]), pack_bf16(a[4], a[5]), pack_bf16(a[6], a[7]));
-  };
+                                                   int nkv, int d, int Lcap, float base) {
   const int t = blockIdx.y;
   const int half8 = d / 16;            // 16-byte chunks per half head
   const int wq = nq * half8, wk = nkv * half8, wv = (vcache != nullptr) ? nkv * (d / 8) : 0;
@@ -197,12 +126,7 @@ __global__ __launch_bounds__(256) void rope_kernel(ts_bf16* __restrict__ q, ts_b
   if (item >= wq + wk) {  // v chunk copy
     int it = item - wq - wk;
     int h = it / (d / 8), c = it % (d / 8);
-    if (SPLITK) {
-      const int col = (nq + nkv) * d + h * d + c * 8;
-      const uint4 val = load8(nullptr, t, col);
-      stg16(q + (size_t)t * q_stride + col, val);
-      if (cache_ok) stg16(vcache + ((sid * nkv + h) * (long)Lcap + p) * d + c * 8, val);
-    } else if (cache_ok) {
+    if (cache_ok) {
       uint4 val = ldg16(v + (size_t)t * kv_stride + h * d + c * 8);
       stg16(vcache + ((sid * nkv + h) * (long)Lcap + p) * d + c * 8, val);
     }
@@ -213,9 +137,8 @@ __global__ __launch_bounds__(256) void rope_kernel(ts_bf16* __restrict__ q, ts_b
   const int h = it / half8, c = it % half8;
   ts_bf16* vec = (is_k ? k + (size_t)t * kv_stride : q + (size_t)t * q_stride) + h * d;
   U4 lo, hi, olo, ohi;
-  const int col = (is_k ? nq * d : 0) + h * d + c * 8;   // column inside the packed buffer (SPLITK only)
-  lo.u = load8(vec + c * 8, t, col);
-  hi.u = load8(vec + d / 2 + c * 8, t, col + d / 2);
+  lo.u = ldg16(vec + c * 8);
+  hi.u = ldg16(vec + d / 2 + c * 8);
   float cs[8], sn[8];
   if (cos_sin != nullptr && p >= 0 && p < table_len) {
     const float4* row = reinterpret_cast<const float4*>(cos_sin + (size_t)p * d);
@@ -256,24 +179,9 @@ int launch_rope(ts_bf16* q, ts_bf16* k, const ts_bf16* v, int q_stride, int kv_s
   if (T == 0) return TS_OK;
   const int items = (nq + nkv) * (d / 16) + (vcache ? nkv * (d / 8) : 0);
   dim3 grid(cdiv(items, 256), T), block(256);
-  const float* np = nullptr;
-  TS_LAUNCH("rope", rope_kernel<false>, grid, block, 0, s, q, k, v, q_stride, kv_stride, pos, seq_id, cos_sin, table_len,
-                     kcache, vcache, nq, nkv, d, Lcap, base, np, 1, 0L);
+  TS_LAUNCH("rope", rope_kernel, grid, block, 0, s, q, k, v, q_stride, kv_stride, pos, seq_id, cos_sin, table_len,
+                     kcache, vcache, nq, nkv, d, Lcap, base);
   TS_LAUNCH_CHECK("rope");
-  return TS_OK;
-}
-
-int launch_rope_splitk(const SplitKPartial& in, ts_bf16* qkv, const int32_t* pos, const int32_t* seq_id,
-                       const float* cos_sin, int table_len, ts_bf16* kcache, ts_bf16* vcache, int T, int nq, int nkv,
-                       int d, int Lcap, float base, hipStream_t s) {
-  if (T == 0) return TS_OK;
-  TS_REQUIRE(kcache != nullptr && vcache != nullptr, TS_ERR_INVALID_ARG, "rope_splitk: the fused form appends to the caches");
-  const int nqkv = (nq + 2 * nkv) * d;
-  const int items = (nq + nkv) * (d / 16) + nkv * (d / 8);
-  dim3 grid(cdiv(items, 256), T), block(256);
-  TS_LAUNCH("rope_splitk", rope_kernel<true>, grid, block, 0, s, qkv, qkv + nq * d, qkv + (nq + nkv) * d, nqkv, nqkv, pos,
-            seq_id, cos_sin, table_len, kcache, vcache, nq, nkv, d, Lcap, base, in.partial, in.S, (long)T * nqkv);
-  TS_LAUNCH_CHECK("rope_splitk");
   return TS_OK;
 }
 

@@ -459,8 +459,6 @@ SkinnyPlan plan_skinny(int M, int N, int K) {
       if (p.S > 16) p.S = 16;
     }
   }
-  if (const char* e = getenv("TS_SKINNY_NT")) p.NT = atoi(e);
-  if (const char* e = getenv("TS_SKINNY_S")) p.S = atoi(e);
   p.kslice = (int)round_up((size_t)cdiv(K, p.S), 128);
   p.S = cdiv(K, p.kslice);
   return p;
@@ -519,7 +517,7 @@ int plan_tiled_split(int M, int N, int K) {
 
 template <int BM, int BN>
 int launch_tiled(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, void* C, bool f32out, int M, int N, int K,
-                 hipStream_t s, int S = 1, float* partial = nullptr, SplitKPartial* defer = nullptr) {
+                 hipStream_t s, int S = 1, float* partial = nullptr) {
   const int tiles_m = cdiv(M, BM), tiles_n = cdiv(N, BN);
   const size_t smem = (size_t)2 * (BM + BN) * 9 * sizeof(uint4);
   const int kslice = (int)round_up((size_t)cdiv(K, S), 64);
@@ -536,11 +534,6 @@ int launch_tiled(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, vo
               tiles_m, tiles_n, partial, kslice);
   }
   TS_LAUNCH_CHECK("gemm_tiled");
-  if (partial != nullptr && defer != nullptr && !f32out) {
-    defer->partial = partial;
-    defer->S = S;
-    return TS_OK;
-  }
   if (partial != nullptr) {
     const long MN = (long)M * N;
     TS_LAUNCH("splitk_reduce", splitk_reduce_kernel, dim3((unsigned)((MN / 2 + 255) / 256)), dim3(256), 0, s, partial,
@@ -565,8 +558,7 @@ size_t gemm_workspace_bytes(int M, int N, int K) {
 }
 
 int launch_gemm(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, void* C, bool f32out, int M, int N, int K,
-                void* ws, size_t ws_bytes, hipStream_t s, SplitKPartial* defer) {
-  if (defer != nullptr) *defer = SplitKPartial();
+                void* ws, size_t ws_bytes, hipStream_t s) {
   if (M == 0) return TS_OK;
   if (use_skinny(M, N)) {
     SkinnyPlan p = plan_skinny(M, N, K);
@@ -580,11 +572,6 @@ int launch_gemm(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, voi
     dim3 grid(cdiv(N, 64 * p.NT), p.S, 1);
     launch_skinny<false>(a, M, p.NT, grid, s);
     TS_LAUNCH_CHECK("gemm_skinny");
-    if (p.S > 1 && defer != nullptr && !f32out) {
-      defer->partial = reinterpret_cast<const float*>(ws);
-      defer->S = p.S;
-      return TS_OK;
-    }
     if (p.S > 1) {
       long MN = (long)M * N;
       TS_LAUNCH("splitk_reduce", splitk_reduce_kernel, dim3((unsigned)((MN / 2 + 255) / 256)), dim3(256), 0, s,
@@ -604,7 +591,7 @@ int launch_gemm(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, voi
   const size_t need = S > 1 ? (size_t)S * M * N * sizeof(float) : 0;
   TS_REQUIRE(need == 0 || (ws != nullptr && ws_bytes >= need), TS_ERR_WORKSPACE,
              "ts_gemm_bf16: workspace %zu bytes < required %zu", ws_bytes, need);
-  return launch_tiled<128, 128>(A, W, residual, C, f32out, M, N, K, s, S, reinterpret_cast<float*>(ws), defer);
+  return launch_tiled<128, 128>(A, W, residual, C, f32out, M, N, K, s, S, reinterpret_cast<float*>(ws));
 }
 
 int launch_moe_gemm(const ts_bf16* A, const int32_t* row_map, int row_div, const ts_bf16* W, const int32_t* offsets,
