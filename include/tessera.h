@@ -276,8 +276,17 @@ int ts_layer_forward(const ts_layer_desc* desc, const ts_layer_weights* w, const
  * rounded up to 256 each, where Tmax/Bmax are the largest over micro-batches.
  * All micro-batches must flag the same boundaries; their T may differ (the
  * layout is computed for each T; slot_stride uses the largest).
+ * copy_mode: TS_PIPE_COPY_SIDE_STREAM sends every flagged boundary as soon as its kernel is enqueued (one
+ * event on the compute stream per boundary); TS_PIPE_COPY_SERIALISED runs the pack kernels on the compute
+ * stream itself (the no-overlap reference); TS_PIPE_COPY_COALESCED sends on the side stream at four
+ * points of the layer (after RoPE, after the second norm, after SwiGLU, at the end), each send carrying
+ * the flagged boundaries produced since the previous one: half the events between the compute kernels
+ * (an event costs the compute stream about 2 us), same bytes in the same slots.
  * The call returns after enqueueing; the caller synchronises the three streams.
  */
+#define TS_PIPE_COPY_SIDE_STREAM 0
+#define TS_PIPE_COPY_SERIALISED 1
+#define TS_PIPE_COPY_COALESCED 2
 typedef struct ts_pipeline ts_pipeline;
 int ts_pipeline_create(const ts_layer_desc* desc, int max_micro_batches, ts_pipeline** out);
 void ts_pipeline_destroy(ts_pipeline* p);
@@ -286,7 +295,7 @@ int ts_pipeline_boundary_layout(const ts_layer_desc* desc, int T, int B, uint64_
 size_t ts_pipeline_slot_stride(const ts_layer_desc* desc, int T, int B, uint64_t boundary_mask);
 int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_io* mb, int n_mb,
                      void* compute_streams[2], void* copy_stream, uint64_t boundary_mask,
-                     int copy_on_compute_stream, void* dev_staging, void* pinned_host,
+                     int copy_mode, void* dev_staging, void* pinned_host,
                      size_t staging_bytes, void* ws, size_t ws_bytes);
 
 /* ---------------------------------------------------------------------------

@@ -74,6 +74,7 @@ class PlanProblem(C.Structure):
 
 
 TS_PLAN_THROUGHPUT, TS_PLAN_LATENCY = 0, 1
+TS_PIPE_COPY_SIDE_STREAM, TS_PIPE_COPY_SERIALISED, TS_PIPE_COPY_COALESCED = 0, 1, 2
 
 
 def _load() -> C.CDLL:
@@ -297,11 +298,13 @@ def ts_pipeline_slot_stride(desc: LayerDesc, T: int, B: int, mask: int) -> int:
 
 
 def ts_pipeline_step(handle: int, weights: LayerWeights, mbs: Sequence[LayerIO], compute_streams, copy_stream,
-                     mask: int, dev_staging, pinned_host, ws, copy_on_compute_stream: bool = False) -> None:
+                     mask: int, dev_staging, pinned_host, ws, copy_on_compute_stream: bool = False,
+                     copy_mode: Optional[int] = None) -> None:
     arr = (LayerIO * len(mbs))(*mbs)
     cs = (_p * 2)(_stream(compute_streams[0]), _stream(compute_streams[1]))
     _check(lib.ts_pipeline_step(handle, C.byref(weights), arr, len(mbs), cs, _stream(copy_stream),
-                                mask & (2 ** 64 - 1), 1 if copy_on_compute_stream else 0, _ptr(dev_staging),
+                                mask & (2 ** 64 - 1),
+                                (1 if copy_on_compute_stream else 0) if copy_mode is None else copy_mode, _ptr(dev_staging),
                                 _ptr(pinned_host), _nbytes(dev_staging), _ptr(ws), _nbytes(ws)))
 
 

@@ -489,7 +489,7 @@ int ts_pipeline_create(const ts_layer_desc* desc, int max_micro_batches, ts_pipe
   const int n = max_micro_batches * TS_NB_MOE + max_micro_batches;
   for (int i = 0; i < n; ++i) {
     hipEvent_t e;
-    hipError_t err = hipEventCreateWithFlags(&e, hipEventDisableTiming);
+    hipError_t err = hipEventCreateWithFlags(&e, hipEventDisableTiming | hipEventReleaseToDevice);
     if (err != hipSuccess) {
       ts_pipeline_destroy(p);
       return check_hip(err, "hipEventCreateWithFlags");
@@ -535,11 +535,13 @@ size_t ts_pipeline_slot_stride(const ts_layer_desc* desc, int T, int B, uint64_t
 }
 
 int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_io* mb, int n_mb,
-                     void* compute_streams[2], void* copy_stream, uint64_t boundary_mask, int copy_on_compute_stream,
+                     void* compute_streams[2], void* copy_stream, uint64_t boundary_mask, int copy_mode,
                      void* dev_staging, void* pinned_host, size_t staging_bytes, void* ws, size_t ws_bytes) {
   TS_REQUIRE(p != nullptr && w != nullptr && mb != nullptr && compute_streams != nullptr, TS_ERR_INVALID_ARG,
              "ts_pipeline_step: null argument");
   TS_REQUIRE(n_mb >= 1 && n_mb <= p->max_mb, TS_ERR_INVALID_ARG, "ts_pipeline_step: n_mb=%d outside [1,%d]", n_mb, p->max_mb);
+  TS_REQUIRE(copy_mode >= TS_PIPE_COPY_SIDE_STREAM && copy_mode <= TS_PIPE_COPY_COALESCED,
+             TS_ERR_INVALID_ARG, "ts_pipeline_step: unknown copy mode %d", copy_mode);
   const ts_layer_desc& d = p->desc;
   const int nb = d.E > 0 ? TS_NB_MOE : TS_NB_DENSE;
   if (nb < 64) boundary_mask &= ((1ull << nb) - 1ull);
@@ -566,7 +568,8 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
     char* wsh = reinterpret_cast<char*>(ws) + (size_t)(i & 1) * half;
     // the workspace half is reused by every second micro-batch: wait until its boundary
     // tensors have been packed before overwriting them
-    if (i >= 2 && boundary_mask != 0 && !copy_on_compute_stream) TS_HIP(hipStreamWaitEvent(s, p->packed_ev[i - 2], 0));
+    if (i >= 2 && boundary_mask != 0 && copy_mode != TS_PIPE_COPY_SERIALISED)
+      TS_HIP(hipStreamWaitEvent(s, p->packed_ev[i - 2], 0));
     const LayerPlan plan = plan_layer(d, mb[i].T, mb[i].B);
     size_t offs[TS_NB_MOE + 1];
     int n = 0;
@@ -575,23 +578,50 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
     char* slot_dev = reinterpret_cast<char*>(dev_staging) + (size_t)i * stride;
     char* slot_host = reinterpret_cast<char*>(pinned_host) + (size_t)i * stride;
     int ordinal = 0;
+    CopySegments pending{};
+    const bool coalesce = copy_mode == TS_PIPE_COPY_COALESCED;
+    const bool serial = copy_mode == TS_PIPE_COPY_SERIALISED;
+    // send what is pending: one event on the compute stream, one pack launch on the copy stream
+    auto flush = [&](int index) -> int {
+      if (pending.n == 0) return TS_OK;
+      hipEvent_t e = p->boundary_ev[(size_t)i * TS_NB_MOE + index];
+      TS_HIP(hipEventRecord(e, s));
+      TS_HIP(hipStreamWaitEvent(copy, e, 0));
+      int rc2 = launch_copy16_multi(pending, slot_dev, slot_host, copy);
+      pending.n = 0;
+      return rc2;
+    };
     auto hook = [&](int index, const void* ptr) -> int {
-      if (!((boundary_mask >> index) & 1)) return TS_OK;
-      const size_t bytes = round_up(plan.bytes[index], 16);
-      const size_t o = offs[ordinal++];
-      hipStream_t target = s;
-      if (!copy_on_compute_stream) {
-        hipEvent_t e = p->boundary_ev[(size_t)i * TS_NB_MOE + index];
-        TS_HIP(hipEventRecord(e, s));
-        TS_HIP(hipStreamWaitEvent(copy, e, 0));
-        target = copy;
+      const bool flagged = (boundary_mask >> index) & 1;
+      if (flagged) {
+        const size_t bytes = round_up(plan.bytes[index], 16);
+        const size_t o = offs[ordinal++];
+        if (coalesce) {
+          pending.src[pending.n] = ptr;
+          pending.dst_off16[pending.n] = o / 16;
+          pending.n16[pending.n] = bytes / 16;
+          ++pending.n;
+        } else {
+          hipStream_t target = s;
+          if (!serial) {
+            hipEvent_t e = p->boundary_ev[(size_t)i * TS_NB_MOE + index];
+            TS_HIP(hipEventRecord(e, s));
+            TS_HIP(hipStreamWaitEvent(copy, e, 0));
+            target = copy;
+          }
+          // one kernel packs the tensor into the device slot and stores it to the pinned host slot
+          return launch_copy16(ptr, slot_dev + o, bytes, target, slot_host + o);
+        }
       }
-      // one kernel packs the tensor into the device slot and stores it to the pinned host slot
-      return launch_copy16(ptr, slot_dev + o, bytes, target, slot_host + o);
+      // coalesced sends leave after RoPE, after the second norm, after SwiGLU and at the end of the layer (the
+      // last one is then only the layer output: the next user of this workspace half waits for it)
+      if (coalesce && (index == TS_B_QKV || index == TS_B_H2 || index == TS_B_ACT || index == nb - 1 || pending.n == 4))
+        return flush(index);
+      return TS_OK;
     };
     rc = layer_forward_impl(d, *w, mb[i], wsh, s, hook);
     if (rc != TS_OK) return rc;
-    if (boundary_mask != 0 && !copy_on_compute_stream) TS_HIP(hipEventRecord(p->packed_ev[i], copy));
+    if (boundary_mask != 0 && copy_mode != TS_PIPE_COPY_SERIALISED) TS_HIP(hipEventRecord(p->packed_ev[i], copy));
   }
   return TS_OK;
 }

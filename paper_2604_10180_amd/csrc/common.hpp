@@ -125,6 +125,14 @@ int launch_rope(ts_bf16* q, ts_bf16* k, const ts_bf16* v, int q_stride, int kv_s
                 const int32_t* seq_id, const float* cos_sin, int table_len, ts_bf16* kcache, ts_bf16* vcache,
                 int T, int nq, int nkv, int d, int Lcap, float base, hipStream_t s);
 int launch_copy16(const void* src, void* dst, size_t bytes, hipStream_t s, void* dst2 = nullptr);
+// up to four tensors packed by one launch into the device slot dst and the host-mapped slot dst2
+struct CopySegments {
+  const void* src[4];
+  size_t dst_off16[4];   // offset inside both slots, in 16-byte units
+  size_t n16[4];         // length in 16-byte units
+  int n;
+};
+int launch_copy16_multi(const CopySegments& segs, void* dst, void* dst2, hipStream_t s);
 
 size_t gemm_workspace_bytes(int M, int N, int K);
 int launch_gemm(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, void* C, bool f32out, int M, int N,

@@ -205,6 +205,29 @@ __global__ __launch_bounds__(256) void copy16_kernel(const uint4* __restrict__ s
   }
 }
 
+// Several boundary tensors in one launch (segments are consecutive in both destination slots).
+__global__ __launch_bounds__(256) void copy16_multi_kernel(CopySegments segs, uint4* __restrict__ dst,
+                                                           uint4* __restrict__ dst2) {
+  const size_t stride = (size_t)gridDim.x * 256;
+  for (int g = 0; g < segs.n; ++g) {
+    const uint4* src = reinterpret_cast<const uint4*>(segs.src[g]);
+    const size_t base = segs.dst_off16[g], n16 = segs.n16[g];
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) {
+      const uint4 v = src[i];
+      dst[base + i] = v;
+      dst2[base + i] = v;
+    }
+  }
+}
+
+int launch_copy16_multi(const CopySegments& segs, void* dst, void* dst2, hipStream_t s) {
+  if (segs.n == 0) return TS_OK;
+  TS_LAUNCH("copy16", copy16_multi_kernel, dim3(32), dim3(256), 0, s, segs, reinterpret_cast<uint4*>(dst),
+            reinterpret_cast<uint4*>(dst2));
+  TS_LAUNCH_CHECK("copy16");
+  return TS_OK;
+}
+
 int launch_copy16(const void* src, void* dst, size_t bytes, hipStream_t s, void* dst2) {
   if (bytes == 0) return TS_OK;
   size_t n16 = bytes / 16;

@@ -315,3 +315,5 @@ def test_70b_pipeline_boundary_copies_overlap(B):
     print("70b pipeline step:", r)
     assert r["side_stream_ms"] <= 1.15 * r["no_copies_ms"], r
     assert r["side_stream_ms"] <= 1.03 * r["serialised_ms"], r
+    assert r["coalesced_ms"] <= 1.08 * r["no_copies_ms"], r
+    assert r["coalesced_ms"] <= 1.03 * r["serialised_ms"], r
