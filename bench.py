@@ -209,6 +209,8 @@ def main():
     ap.add_argument("--pipeline", action="store_true",
                     help="also time ts_pipeline_step over the workload's micro-batches: boundary copies off, "
                          "on the side stream, and serialised on the compute streams")
+    ap.add_argument("--graph", action="store_true",
+                    help="also time the layer replayed from HIP graphs (one captured graph per rotated copy)")
     ap.add_argument("--plan", action="store_true",
                     help="also run the policy planner on the measured kernel-group times against modelled second GPUs")
     ap.add_argument("--calibration-copy", action="store_true",
@@ -343,6 +345,24 @@ def main():
 
     if args.plan:
         result["plan"] = plan_section(B, wl, desc, kernels)
+
+    if args.graph:
+        side = torch.cuda.Stream()
+        graphs = []
+        for c in range(len(sets)):
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=side):
+                step(c)
+            graphs.append(g)
+        for i in range(args.warmup):
+            graphs[i % len(graphs)].replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            graphs[i % len(graphs)].replay()
+        torch.cuda.synchronize()
+        g_ms = (time.perf_counter() - t0) * 1e3 / args.steps
+        result["graph_replay"] = {"ms_per_step": round(g_ms, 5), "tokens_per_s": round(T / (g_ms * 1e-3), 1)}
 
     if not args.no_cpu_baseline:
         from oracle import decoder_layer as O

@@ -253,6 +253,10 @@ int ts_layer_boundary(const ts_layer_desc* desc, int T, int B, int index, size_t
 /* Where the MoE routing outputs live inside the workspace (host-only arithmetic):
  * offsets of logits f32[T,E], topk_idx i32[T,k], topk_w f32[T,k], counts i32[E], offsets i32[E+1], perm i32[T*k]. */
 int ts_layer_moe_buffers(const ts_layer_desc* desc, int T, int B, size_t ws_offsets[6]);
+/* Enqueues the whole layer on `stream` and returns; kernels only: no allocation, no memset, no copy-engine
+ * command, no host synchronisation, so the call may be recorded into a HIP graph by stream capture and
+ * replayed (sizes, pointers and sequence lengths are those of the capture; the lengths are read from
+ * device memory at run time). */
 int ts_layer_forward(const ts_layer_desc* desc, const ts_layer_weights* w, const ts_layer_io* io,
                      void* ws, size_t ws_bytes, void* stream);
 

@@ -233,3 +233,48 @@ def test_pipeline_step_matches_single_stream_and_oracle(B, mask):
         assert got.numel() == ref.size
         if ref.size:
             assert_close(got, ref, f"micro-batch {i} boundary stream")
+
+
+@pytest.mark.parametrize("moe", [False, True])
+def test_layer_forward_replays_from_a_hip_graph(B, moe):
+    """The layer enqueues kernels only (no allocation, no memset, no host synchronisation), so it can be
+    captured once and replayed.  Every replay is checked against the eager result, with eager work and
+    synchronisations between the replays."""
+    shape = WL.LayerShape(H=256, nq=4, nkv=2, d=64, F=688, E=4 if moe else 0, k=2 if moe else 0)
+    wl = WL.Workload("graph", shape, "decode", B=6, ctx=128)
+    weights, io, _ = WL.build(wl, seed=11, ctx_lens=[70, 1, 128, 33, 5, 90])
+    s = wl.shape
+    Lcap = io["kcache"].shape[2]
+    T = Bs = wl.B
+    wd = {k: v.to(DEV) for k, v in weights.items()}
+    desc = B.make_desc(s, Lcap, "decode")
+    wts = B.make_weights(wd)
+    nbytes = B.ts_layer_workspace_bytes(desc, T, Bs)
+
+    def fresh():
+        iod = {k: v.clone().to(DEV) for k, v in io.items()}
+        return iod, torch.zeros(T, s.H, dtype=torch.bfloat16, device=DEV), torch.zeros(nbytes, dtype=torch.uint8, device=DEV)
+
+    iod_e, out_e, ws_e = fresh()
+    B.ts_layer_forward(desc, wts, B.make_io(iod_e, out_e, T, Bs), ws_e)
+    torch.cuda.synchronize()
+    iod_g, out_g, ws_g = fresh()
+    io_g = B.make_io(iod_g, out_g, T, Bs)
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        B.ts_layer_forward(desc, wts, io_g, ws_g)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        out_g.zero_()
+        ws_g.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out_g, out_e), f"replay {rep}: output differs from the eager layer"
+        assert torch.equal(iod_g["kcache"], iod_e["kcache"]) and torch.equal(iod_g["vcache"], iod_e["vcache"])
+        # eager work on other buffers between the replays
+        iod_x, out_x, ws_x = fresh()
+        B.ts_layer_forward(desc, wts, B.make_io(iod_x, out_x, T, Bs), ws_x)
+        torch.cuda.synchronize()
+        assert torch.equal(out_x, out_e)
