@@ -138,6 +138,7 @@ def plan_section(B, wl, desc, kernels, n_layers=4, link_GBps=25.0, link_latency_
             tic = time.perf_counter()
             place, val, Tg, Mg, opt = B.ts_plan_policy(t, edges, bw, lat, obj, node_limit=2_000_000)
             solve_ms = (time.perf_counter() - tic) * 1e3
+            lb = B.ts_plan_lower_bound(t, edges, bw, lat, obj)
             first = place[:nb] + [place[nb] if n_layers > 1 else place[nb - 1]]
             try:
                 mask = B.ts_layer_cut_mask(desc, first)
@@ -146,7 +147,8 @@ def plan_section(B, wl, desc, kernels, n_layers=4, link_GBps=25.0, link_latency_
             entry[oname] = {"value_us": round(val * 1e6, 2), "mi355x_alone_us": round(sum(t0) * n_layers * 1e6, 2),
                             "T_g_us": [round(v * 1e6, 2) for v in Tg], "M_g_us": [round(v * 1e6, 2) for v in Mg],
                             "placement_layer0": place[:nb], "on_modelled_gpu": int(sum(place)),
-                            "boundary_mask_layer0": mask, "proved_optimal": opt, "solve_ms": round(solve_ms, 2)}
+                            "boundary_mask_layer0": mask, "proved_optimal": opt, "solve_ms": round(solve_ms, 2),
+                            "gap_to_lower_bound": round(max(0.0, (val - lb) / val), 6)}
         out[gname] = entry
     return out
 

@@ -394,6 +394,12 @@ typedef struct ts_plan_problem {
 int ts_plan_policy(const ts_plan_problem* problem, int objective, int64_t node_limit,
                    int32_t* placement, double* value, double* T_g, double* M_g,
                    int* proved_optimal);
+/* A lower bound of the optimum of `objective` that needs no search: the sum over kernels of their fastest
+ * time for the latency objective; for the throughput objective the larger of that sum divided by the number
+ * of GPUs and, with two GPUs, the makespan of the best fractional split of the kernels without communication.
+ * (value - bound) / value bounds the optimality gap of a ts_plan_policy result that was stopped by its
+ * node limit. */
+int ts_plan_lower_bound(const ts_plan_problem* problem, int objective, double* lower_bound);
 
 /* ---------------------------------------------------------------------------
  * Online monitor (Sec. 3.4).  HOST-only, O(1) state, not thread-safe.

@@ -26,7 +26,7 @@ EXPORTS = [
     "ts_attention_decode", "ts_attention_prefill", "ts_swiglu", "ts_moe_route", "ts_moe_gemm", "ts_moe_combine",
     "ts_layer_workspace_bytes", "ts_layer_boundary", "ts_layer_moe_buffers", "ts_layer_forward",
     "ts_pipeline_create", "ts_pipeline_destroy", "ts_pipeline_boundary_layout", "ts_pipeline_slot_stride",
-    "ts_pipeline_step", "ts_ddg_build", "ts_layer_ddg", "ts_layer_node_name", "ts_layer_cut_mask", "ts_plan_policy",
+    "ts_pipeline_step", "ts_ddg_build", "ts_layer_ddg", "ts_layer_node_name", "ts_layer_cut_mask", "ts_plan_policy", "ts_plan_lower_bound",
     "ts_monitor_create", "ts_monitor_destroy", "ts_monitor_record", "ts_monitor_advance",
 ]
 
@@ -128,6 +128,7 @@ lib.ts_layer_node_name.argtypes = [C.POINTER(LayerDesc), _i]
 lib.ts_layer_cut_mask.argtypes = [C.POINTER(LayerDesc), C.POINTER(C.c_int32), C.POINTER(_u64)]
 lib.ts_plan_policy.argtypes = [C.POINTER(PlanProblem), _i, C.c_int64, C.POINTER(C.c_int32), C.POINTER(C.c_double),
                                C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(_i)]
+lib.ts_plan_lower_bound.argtypes = [C.POINTER(PlanProblem), _i, C.POINTER(C.c_double)]
 lib.ts_monitor_create.argtypes = [C.c_double, C.c_double, _i, C.POINTER(_p)]
 lib.ts_monitor_destroy.argtypes = [_p]
 lib.ts_monitor_record.argtypes = [_p, C.c_double, C.c_double, C.POINTER(C.c_double), _i, C.c_double]
@@ -357,17 +358,29 @@ def ts_layer_cut_mask(desc: LayerDesc, placement: Sequence[int]) -> int:
     return mask.value
 
 
-def ts_plan_policy(t, edges, bw, lat, objective: int, node_limit: int = 0):
-    """t: [K][G] seconds; edges: [(src, dst, bytes[, cross])]; bw, lat: [G][G].
-    Returns (placement, value, T_g, M_g, proved_optimal)."""
+def _plan_problem(t, edges, bw, lat):
     K, G = len(t), len(t[0])
     flat = lambda m: (C.c_double * (len(m) * len(m[0])))(*[float(v) for row in m for v in row])
     ta = flat(t)
     ea = (DdgEdge * max(1, len(edges)))()
     for i, e in enumerate(edges):
         ea[i] = DdgEdge(e[0], e[1], int(e[2]), e[3] if len(e) > 3 else 0, 0)
-    prob = PlanProblem(K, G, len(edges), 0, ta, ea, flat(bw) if bw is not None else None,
-                       flat(lat) if lat is not None else None)
+    ba, la = (flat(bw) if bw is not None else None), (flat(lat) if lat is not None else None)
+    return PlanProblem(K, G, len(edges), 0, ta, ea, ba, la), (ta, ea, ba, la)
+
+
+def ts_plan_lower_bound(t, edges, bw, lat, objective: int) -> float:
+    prob, _keep = _plan_problem(t, edges, bw, lat)
+    out = C.c_double()
+    _check(lib.ts_plan_lower_bound(C.byref(prob), objective, C.byref(out)))
+    return out.value
+
+
+def ts_plan_policy(t, edges, bw, lat, objective: int, node_limit: int = 0):
+    """t: [K][G] seconds; edges: [(src, dst, bytes[, cross])]; bw, lat: [G][G].
+    Returns (placement, value, T_g, M_g, proved_optimal)."""
+    K, G = len(t), len(t[0])
+    prob, _keep = _plan_problem(t, edges, bw, lat)
     place, val, opt = (C.c_int32 * K)(), C.c_double(), _i()
     Tg, Mg = (C.c_double * G)(), (C.c_double * G)()
     _check(lib.ts_plan_policy(C.byref(prob), objective, node_limit, place, C.byref(val), Tg, Mg, C.byref(opt)))

@@ -500,15 +500,16 @@ int ts_layer_cut_mask(const ts_layer_desc* desc, const int32_t* placement, uint6
   return TS_OK;
 }
 
-int ts_plan_policy(const ts_plan_problem* pr, int objective, int64_t node_limit, int32_t* placement, double* value,
-                   double* T_g, double* M_g, int* proved_optimal) {
-  TS_REQUIRE(pr != nullptr && placement != nullptr && value != nullptr, TS_ERR_INVALID_ARG, "ts_plan_policy: null argument");
+// Shared by the two planner entry points: validates, searches, and reports a lower bound of the optimum.
+static int plan_impl(const ts_plan_problem* pr, int objective, int64_t node_limit, int32_t* placement, double* value,
+                     double* T_g, double* M_g, int* proved_optimal, double* lower_bound, const char* who) {
+  TS_REQUIRE(pr != nullptr, TS_ERR_INVALID_ARG, "%s: null problem", who);
   TS_REQUIRE(pr->n_kernels >= 1 && pr->n_gpus >= 1 && pr->n_gpus <= 64 && pr->n_edges >= 0, TS_ERR_INVALID_ARG,
-             "ts_plan_policy: bad sizes (kernels %d, gpus %d, edges %d)", pr->n_kernels, pr->n_gpus, pr->n_edges);
+             "%s: bad sizes (kernels %d, gpus %d, edges %d)", who, pr->n_kernels, pr->n_gpus, pr->n_edges);
   TS_REQUIRE(pr->t != nullptr && (pr->n_edges == 0 || pr->edges != nullptr) && (pr->n_gpus == 1 || (pr->bw && pr->lat)),
-             TS_ERR_INVALID_ARG, "ts_plan_policy: null table");
+             TS_ERR_INVALID_ARG, "%s: null table", who);
   TS_REQUIRE(objective == TS_PLAN_THROUGHPUT || objective == TS_PLAN_LATENCY, TS_ERR_INVALID_ARG,
-             "ts_plan_policy: unknown objective %d", objective);
+             "%s: unknown objective %d", who, objective);
   Problem p;
   p.K = pr->n_kernels;
   p.G = pr->n_gpus;
@@ -520,36 +521,42 @@ int ts_plan_policy(const ts_plan_problem* pr, int objective, int64_t node_limit,
     const ts_ddg_edge& ed = pr->edges[e];
     if (ed.cross_iteration) continue;                      // replicated buffers: no cost in the objectives
     TS_REQUIRE(ed.src >= 0 && ed.src < ed.dst && ed.dst < p.K, TS_ERR_INVALID_ARG,
-               "ts_plan_policy: edge %d (%d -> %d) does not follow execution order", e, ed.src, ed.dst);
+               "%s: edge %d (%d -> %d) does not follow execution order", who, e, ed.src, ed.dst);
     p.in[ed.dst].push_back({ed.src, (double)ed.bytes});
   }
   for (int i = 0; i < p.K * p.G; ++i)
-    TS_REQUIRE(pr->t[i] >= 0.0 && std::isfinite(pr->t[i]), TS_ERR_INVALID_ARG, "ts_plan_policy: negative or non-finite latency");
+    TS_REQUIRE(pr->t[i] >= 0.0 && std::isfinite(pr->t[i]), TS_ERR_INVALID_ARG, "%s: negative or non-finite latency", who);
+
+  BnB s{p, objective, node_limit > 0 ? node_limit : (int64_t)50'000'000};
+  s.T.assign(p.G, 0.0);
+  s.M.assign(p.G, 0.0);
+  s.place.assign(p.K, 0);
+  s.rem_min.assign(p.K + 1, 0.0);
+  for (int k = p.K - 1; k >= 0; --k) {
+    double mn = p.t[k * p.G];
+    for (int g = 1; g < p.G; ++g) mn = std::min(mn, p.t[k * p.G + g]);
+    s.rem_min[k] = s.rem_min[k + 1] + mn;
+  }
+  if (p.G == 2) {
+    s.rem0.assign(p.K + 1, 0.0);
+    for (int k = p.K - 1; k >= 0; --k) s.rem0[k] = s.rem0[k + 1] + p.t[k * 2];
+    s.by_ratio.resize(p.K);
+    for (int k = 0; k < p.K; ++k) s.by_ratio[k] = k;
+    auto ratio = [&](int x) {
+      return p.t[x * 2] > 0.0 ? p.t[x * 2 + 1] / p.t[x * 2] : std::numeric_limits<double>::infinity();
+    };
+    std::stable_sort(s.by_ratio.begin(), s.by_ratio.end(), [&](int x, int y) { return ratio(x) < ratio(y); });
+  }
+  const double root_bound = s.bound(0);                    // nothing placed yet: a bound of the optimum itself
+  if (placement == nullptr) {                              // bound only
+    *lower_bound = root_bound;
+    return TS_OK;
+  }
 
   std::vector<int32_t> best_place;
   double best = 0.0;
   bool optimal = true;
   if (!(objective == TS_PLAN_LATENCY && plan_latency_dp(p, best_place, best))) {
-    BnB s{p, objective, node_limit > 0 ? node_limit : (int64_t)50'000'000};
-    s.T.assign(p.G, 0.0);
-    s.M.assign(p.G, 0.0);
-    s.place.assign(p.K, 0);
-    s.rem_min.assign(p.K + 1, 0.0);
-    for (int k = p.K - 1; k >= 0; --k) {
-      double mn = p.t[k * p.G];
-      for (int g = 1; g < p.G; ++g) mn = std::min(mn, p.t[k * p.G + g]);
-      s.rem_min[k] = s.rem_min[k + 1] + mn;
-    }
-    if (p.G == 2) {
-      s.rem0.assign(p.K + 1, 0.0);
-      for (int k = p.K - 1; k >= 0; --k) s.rem0[k] = s.rem0[k + 1] + p.t[k * 2];
-      s.by_ratio.resize(p.K);
-      for (int k = 0; k < p.K; ++k) s.by_ratio[k] = k;
-      auto ratio = [&](int x) {
-        return p.t[x * 2] > 0.0 ? p.t[x * 2 + 1] / p.t[x * 2] : std::numeric_limits<double>::infinity();
-      };
-      std::stable_sort(s.by_ratio.begin(), s.by_ratio.end(), [&](int x, int y) { return ratio(x) < ratio(y); });
-    }
     // incumbent: the best single GPU (always feasible, no communication)
     for (int g = 0; g < p.G; ++g) {
       double v = 0.0;
@@ -585,7 +592,19 @@ int ts_plan_policy(const ts_plan_problem* pr, int objective, int64_t node_limit,
   if (T_g) std::copy(T.begin(), T.end(), T_g);
   if (M_g) std::copy(M.begin(), M.end(), M_g);
   if (proved_optimal) *proved_optimal = optimal ? 1 : 0;
+  if (lower_bound) *lower_bound = optimal ? v : std::min(v, root_bound);
   return TS_OK;
+}
+
+int ts_plan_policy(const ts_plan_problem* pr, int objective, int64_t node_limit, int32_t* placement, double* value,
+                   double* T_g, double* M_g, int* proved_optimal) {
+  TS_REQUIRE(placement != nullptr && value != nullptr, TS_ERR_INVALID_ARG, "ts_plan_policy: null argument");
+  return plan_impl(pr, objective, node_limit, placement, value, T_g, M_g, proved_optimal, nullptr, "ts_plan_policy");
+}
+
+int ts_plan_lower_bound(const ts_plan_problem* pr, int objective, double* lower_bound) {
+  TS_REQUIRE(lower_bound != nullptr, TS_ERR_INVALID_ARG, "ts_plan_lower_bound: null argument");
+  return plan_impl(pr, objective, 0, nullptr, nullptr, nullptr, nullptr, nullptr, lower_bound, "ts_plan_lower_bound");
 }
 
 }  // extern "C"

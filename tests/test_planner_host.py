@@ -153,6 +153,22 @@ def test_planner_attains_the_bruteforce_optimum(objective, n_g):
         assert P.policy_objective(place, t, edges, bw, lat, n_g, objective) == pytest.approx(val, rel=1e-12)
         T0, M0 = P.policy_terms(place, t, edges, bw, lat, n_g)
         assert Tg == pytest.approx(T0) and Mg == pytest.approx(M0)
+        assert B.ts_plan_lower_bound(t, el, bw, lat, OBJ[objective]) <= want * (1 + 1e-12)
+
+
+def test_lower_bound_is_tight_where_the_optimum_is_known():
+    INF_ = float("inf")
+    free = [[INF_, INF_], [INF_, INF_]]
+    zero = [[0.0, 0.0], [0.0, 0.0]]
+    t = [[3.0, 4.0], [2.0, 1.0], [5.0, 5.5]]
+    assert B.ts_plan_lower_bound(t, [], free, zero, B.TS_PLAN_LATENCY) == pytest.approx(3.0 + 1.0 + 5.0)
+    # two identical GPUs, kernels that split evenly: the fractional bound is the optimum
+    t = [[2.0, 2.0]] * 6
+    assert B.ts_plan_lower_bound(t, [], free, zero, B.TS_PLAN_THROUGHPUT) == pytest.approx(6.0)
+    assert B.ts_plan_policy(t, [], free, zero, B.TS_PLAN_THROUGHPUT)[1] == pytest.approx(6.0)
+    # a GPU that is 3x slower takes a quarter of the (divisible) work: makespan = 3/4 of the fast GPU alone
+    t = [[1.0, 3.0]] * 8
+    assert B.ts_plan_lower_bound(t, [], free, zero, B.TS_PLAN_THROUGHPUT) == pytest.approx(6.0)
 
 
 def test_planner_ignores_cross_iteration_edges_and_rejects_bad_input():
