@@ -194,6 +194,28 @@ def time_pipeline(B, torch, wl, desc, dev_set, io_cpu, dev, steps, warmup):
             out[name + "_ms"] = round((time.perf_counter() - t0) * 1e3 / steps, 4)
     finally:
         B.ts_pipeline_destroy(pipe)
+    # background replication of the KV delta on a fourth stream, on top of the coalesced sends
+    pipe = B.ts_pipeline_create(desc, n_mb)
+    try:
+        dstride = B.ts_pipeline_kv_delta_stride(desc, per)
+        ddev = torch.zeros(dstride * n_mb, dtype=torch.uint8, device=dev)
+        dhost = torch.zeros(dstride * n_mb, dtype=torch.uint8).pin_memory()
+        dstream = torch.cuda.Stream()
+        B.ts_pipeline_set_kv_delta(pipe, dstream, ddev, dhost)
+
+        def one_delta():
+            B.ts_pipeline_step(pipe, wts, mbs, streams, copy, full, staging, host, ws, copy_mode=B.TS_PIPE_COPY_COALESCED)
+        for _ in range(warmup):
+            one_delta()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            one_delta()
+        torch.cuda.synchronize()
+        out["coalesced_with_kv_delta_ms"] = round((time.perf_counter() - t0) * 1e3 / steps, 4)
+        out["kv_delta_bytes_per_step"] = int(per * 2 * s.nkv * s.d * 2 * n_mb)
+    finally:
+        B.ts_pipeline_destroy(pipe)
     out["tokens_per_s_side_stream"] = round(wl.B / (out["side_stream_ms"] * 1e-3), 1)
     out["overlap_ratio"] = round(out["side_stream_ms"] / out["no_copies_ms"], 4)
     out["overlap_ratio_coalesced"] = round(out["coalesced_ms"] / out["no_copies_ms"], 4)

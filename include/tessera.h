@@ -286,7 +286,9 @@ int ts_layer_forward(const ts_layer_desc* desc, const ts_layer_weights* w, const
  * points of the layer (after RoPE, after the second norm, after SwiGLU, at the end), each send carrying
  * the flagged boundaries produced since the previous one: half the events between the compute kernels
  * (an event costs the compute stream about 2 us), same bytes in the same slots.
- * The call returns after enqueueing; the caller synchronises the three streams.
+ * The call returns after enqueueing; steps may be enqueued back to back (each waits for the transfers of
+ * the previous one that still read its workspace half); the caller synchronises the streams before it
+ * reads the slots or frees the buffers.
  */
 #define TS_PIPE_COPY_SIDE_STREAM 0
 #define TS_PIPE_COPY_SERIALISED 1
@@ -297,6 +299,18 @@ void ts_pipeline_destroy(ts_pipeline* p);
 int ts_pipeline_boundary_layout(const ts_layer_desc* desc, int T, int B, uint64_t boundary_mask,
                                 size_t* offsets /* host, [n+1] */, int* n_boundaries);
 size_t ts_pipeline_slot_stride(const ts_layer_desc* desc, int T, int B, uint64_t boundary_mask);
+/* Background replication of the KV-cache delta (Sec. 4: buffers with a cross-iteration dependency keep a
+ * replica per GPU and the rows written in an iteration are propagated asynchronously, apart from the
+ * dependency transfers).  Once set, every ts_pipeline_step also packs, for each micro-batch i, the K and V
+ * rows its tokens append to the cache into slot i of dev_slots and host_slots (device memory and
+ * device-addressable pinned host memory, slot stride ts_pipeline_kv_delta_stride(desc, Tmax), layout
+ * [T][K row of nkv*d | V row of nkv*d] bf16, keys already rotated) with a small kernel on delta_stream,
+ * which the compute streams wait for only before the workspace half is reused.  All streams here have
+ * the default priority.  Passing dev_slots = host_slots = NULL switches it off.  `bytes` is the size of
+ * each of the two buffers; ts_pipeline_step checks it against n_mb * stride. */
+size_t ts_pipeline_kv_delta_stride(const ts_layer_desc* desc, int T);
+int ts_pipeline_set_kv_delta(ts_pipeline* p, void* delta_stream, void* dev_slots, void* host_slots,
+                             size_t bytes);
 int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_io* mb, int n_mb,
                      void* compute_streams[2], void* copy_stream, uint64_t boundary_mask,
                      int copy_mode, void* dev_staging, void* pinned_host,

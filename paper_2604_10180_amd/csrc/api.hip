@@ -475,6 +475,17 @@ struct ts_pipeline {
   int max_mb;
   std::vector<hipEvent_t> boundary_ev;  // [max_mb][TS_NB_MOE]
   std::vector<hipEvent_t> packed_ev;    // [max_mb]
+  std::vector<hipEvent_t> kv_ready_ev;  // [max_mb] compute stream: K/V rows of the step are in the projection buffer
+  std::vector<hipEvent_t> kv_sent_ev;   // [max_mb] delta stream: rows have left
+  // background replication of the rows appended to the KV cache (off while delta_stream is null)
+  hipStream_t delta_stream = nullptr;
+  char* delta_dev = nullptr;
+  char* delta_host = nullptr;
+  size_t delta_bytes = 0;
+  bool delta_on = false;
+  // what the previous step left in flight on the side streams, per workspace half (-1: nothing)
+  int prev_packed[2] = {-1, -1};
+  int prev_kv_sent[2] = {-1, -1};
 };
 
 int ts_pipeline_create(const ts_layer_desc* desc, int max_micro_batches, ts_pipeline** out) {
@@ -486,7 +497,8 @@ int ts_pipeline_create(const ts_layer_desc* desc, int max_micro_batches, ts_pipe
   TS_REQUIRE(p != nullptr, TS_ERR_INVALID_ARG, "ts_pipeline_create: out of host memory");
   p->desc = *desc;
   p->max_mb = max_micro_batches;
-  const int n = max_micro_batches * TS_NB_MOE + max_micro_batches;
+  const int nbe = max_micro_batches * TS_NB_MOE;
+  const int n = nbe + 3 * max_micro_batches;
   for (int i = 0; i < n; ++i) {
     hipEvent_t e;
     hipError_t err = hipEventCreateWithFlags(&e, hipEventDisableTiming | hipEventReleaseToDevice);
@@ -494,8 +506,10 @@ int ts_pipeline_create(const ts_layer_desc* desc, int max_micro_batches, ts_pipe
       ts_pipeline_destroy(p);
       return check_hip(err, "hipEventCreateWithFlags");
     }
-    if (i < max_micro_batches * TS_NB_MOE) p->boundary_ev.push_back(e);
-    else p->packed_ev.push_back(e);
+    if (i < nbe) p->boundary_ev.push_back(e);
+    else if (i < nbe + max_micro_batches) p->packed_ev.push_back(e);
+    else if (i < nbe + 2 * max_micro_batches) p->kv_ready_ev.push_back(e);
+    else p->kv_sent_ev.push_back(e);
   }
   *out = p;
   return TS_OK;
@@ -505,7 +519,30 @@ void ts_pipeline_destroy(ts_pipeline* p) {
   if (p == nullptr) return;
   for (hipEvent_t e : p->boundary_ev) (void)hipEventDestroy(e);
   for (hipEvent_t e : p->packed_ev) (void)hipEventDestroy(e);
+  for (hipEvent_t e : p->kv_ready_ev) (void)hipEventDestroy(e);
+  for (hipEvent_t e : p->kv_sent_ev) (void)hipEventDestroy(e);
   delete p;
+}
+
+size_t ts_pipeline_kv_delta_stride(const ts_layer_desc* desc, int T) {
+  if (desc == nullptr || T < 0 || validate_desc(desc, "ts_pipeline_kv_delta_stride") != TS_OK) return 0;
+  return round_up((size_t)T * 2 * desc->nkv * desc->d * sizeof(ts_bf16), 256);
+}
+
+int ts_pipeline_set_kv_delta(ts_pipeline* p, void* delta_stream, void* dev_slots, void* host_slots, size_t bytes) {
+  TS_REQUIRE(p != nullptr, TS_ERR_INVALID_ARG, "ts_pipeline_set_kv_delta: null pipeline");
+  if (dev_slots == nullptr && host_slots == nullptr) {
+    p->delta_on = false;
+    return TS_OK;
+  }
+  TS_REQUIRE(dev_slots != nullptr && host_slots != nullptr && aligned16(dev_slots) && aligned16(host_slots), TS_ERR_INVALID_ARG,
+             "ts_pipeline_set_kv_delta: both slot buffers are needed, 16-byte aligned");
+  p->delta_stream = as_stream(delta_stream);
+  p->delta_dev = reinterpret_cast<char*>(dev_slots);
+  p->delta_host = reinterpret_cast<char*>(host_slots);
+  p->delta_bytes = bytes;
+  p->delta_on = true;
+  return TS_OK;
 }
 
 int ts_pipeline_boundary_layout(const ts_layer_desc* desc, int T, int B, uint64_t boundary_mask, size_t* offsets,
@@ -562,6 +599,9 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
              "ts_pipeline_step: buffer not 16-byte aligned");
   hipStream_t cs[2] = {as_stream(compute_streams[0]), as_stream(compute_streams[1])};
   hipStream_t copy = as_stream(copy_stream);
+  const size_t dstride = ts_pipeline_kv_delta_stride(&d, Tmax);
+  TS_REQUIRE(!p->delta_on || p->delta_bytes >= dstride * (size_t)n_mb, TS_ERR_WORKSPACE,
+             "ts_pipeline_step: KV delta slots %zu bytes < required %zu", p->delta_bytes, dstride * (size_t)n_mb);
 
   for (int i = 0; i < n_mb; ++i) {
     hipStream_t s = cs[i & 1];
@@ -570,6 +610,11 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
     // tensors have been packed before overwriting them
     if (i >= 2 && boundary_mask != 0 && copy_mode != TS_PIPE_COPY_SERIALISED)
       TS_HIP(hipStreamWaitEvent(s, p->packed_ev[i - 2], 0));
+    if (i >= 2 && p->delta_on) TS_HIP(hipStreamWaitEvent(s, p->kv_sent_ev[i - 2], 0));   // its rows sit in that half
+    if (i < 2) {   // steps may follow each other without a host synchronisation: the previous step's last users
+      if (p->prev_packed[i] >= 0) TS_HIP(hipStreamWaitEvent(s, p->packed_ev[p->prev_packed[i]], 0));
+      if (p->prev_kv_sent[i] >= 0) TS_HIP(hipStreamWaitEvent(s, p->kv_sent_ev[p->prev_kv_sent[i]], 0));
+    }
     const LayerPlan plan = plan_layer(d, mb[i].T, mb[i].B);
     size_t offs[TS_NB_MOE + 1];
     int n = 0;
@@ -592,6 +637,18 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
       return rc2;
     };
     auto hook = [&](int index, const void* ptr) -> int {
+      if (index == TS_B_QKV && p->delta_on) {
+        // the K and V rows this step appends to the cache are columns [nq d, (nq + 2 nkv) d) of the projection
+        // buffer: one strided pack on the delta stream, behind an event of its own
+        TS_HIP(hipEventRecord(p->kv_ready_ev[i], s));
+        TS_HIP(hipStreamWaitEvent(p->delta_stream, p->kv_ready_ev[i], 0));
+        const int nqkv = (d.nq + 2 * d.nkv) * d.d;
+        int rc2 = launch_copy_rows(reinterpret_cast<const ts_bf16*>(ptr) + (size_t)d.nq * d.d, (size_t)nqkv * sizeof(ts_bf16),
+                                   (size_t)2 * d.nkv * d.d * sizeof(ts_bf16), mb[i].T, p->delta_dev + (size_t)i * dstride,
+                                   p->delta_host + (size_t)i * dstride, p->delta_stream);
+        if (rc2 != TS_OK) return rc2;
+        TS_HIP(hipEventRecord(p->kv_sent_ev[i], p->delta_stream));
+      }
       const bool flagged = (boundary_mask >> index) & 1;
       if (flagged) {
         const size_t bytes = round_up(plan.bytes[index], 16);
@@ -622,6 +679,11 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
     rc = layer_forward_impl(d, *w, mb[i], wsh, s, hook);
     if (rc != TS_OK) return rc;
     if (boundary_mask != 0 && copy_mode != TS_PIPE_COPY_SERIALISED) TS_HIP(hipEventRecord(p->packed_ev[i], copy));
+  }
+  for (int h = 0; h < 2; ++h) {
+    const int last = n_mb - 1 - (((n_mb - 1) & 1) != h ? 1 : 0);   // last micro-batch that used half h
+    p->prev_packed[h] = (last >= 0 && boundary_mask != 0 && copy_mode != TS_PIPE_COPY_SERIALISED) ? last : -1;
+    p->prev_kv_sent[h] = (last >= 0 && p->delta_on) ? last : -1;
   }
   return TS_OK;
 }

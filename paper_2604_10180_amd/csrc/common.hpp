@@ -133,6 +133,8 @@ struct CopySegments {
   int n;
 };
 int launch_copy16_multi(const CopySegments& segs, void* dst, void* dst2, hipStream_t s);
+int launch_copy_rows(const void* src, size_t src_stride_bytes, size_t row_bytes, int rows, void* dst, void* dst2,
+                     hipStream_t s);
 
 size_t gemm_workspace_bytes(int M, int N, int K);
 int launch_gemm(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, void* C, bool f32out, int M, int N,

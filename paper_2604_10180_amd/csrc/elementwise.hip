@@ -228,6 +228,32 @@ int launch_copy16_multi(const CopySegments& segs, void* dst, void* dst2, hipStre
   return TS_OK;
 }
 
+// `rows` rows of row16 16-byte units each, src_stride16 units apart, packed densely into dst and dst2.
+__global__ __launch_bounds__(256) void copy_rows_kernel(const uint4* __restrict__ src, size_t src_stride16, size_t row16,
+                                                        size_t rows, uint4* __restrict__ dst, uint4* __restrict__ dst2) {
+  const size_t total = rows * row16, stride = (size_t)gridDim.x * 256;
+  for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < total; i += stride) {
+    const size_t r = i / row16, c = i - r * row16;
+    const uint4 v = src[r * src_stride16 + c];
+    dst[i] = v;
+    dst2[i] = v;
+  }
+}
+
+int launch_copy_rows(const void* src, size_t src_stride_bytes, size_t row_bytes, int rows, void* dst, void* dst2,
+                     hipStream_t s) {
+  if (rows == 0 || row_bytes == 0) return TS_OK;
+  TS_REQUIRE(src_stride_bytes % 16 == 0 && row_bytes % 16 == 0 && aligned16(src), TS_ERR_INVALID_ARG,
+             "copy_rows: rows must be whole 16-byte units");
+  const size_t total = (size_t)rows * (row_bytes / 16);
+  unsigned blocks = (unsigned)((total + 255) / 256);
+  if (blocks > 8) blocks = 8;   // background traffic: a few workgroups, it must not take CUs from the compute streams
+  TS_LAUNCH("copy_rows", copy_rows_kernel, dim3(blocks), dim3(256), 0, s, reinterpret_cast<const uint4*>(src),
+            src_stride_bytes / 16, row_bytes / 16, (size_t)rows, reinterpret_cast<uint4*>(dst), reinterpret_cast<uint4*>(dst2));
+  TS_LAUNCH_CHECK("copy_rows");
+  return TS_OK;
+}
+
 int launch_copy16(const void* src, void* dst, size_t bytes, hipStream_t s, void* dst2) {
   if (bytes == 0) return TS_OK;
   size_t n16 = bytes / 16;

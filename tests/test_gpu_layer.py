@@ -191,9 +191,18 @@ def _pipeline_case(B, wl, weights, io, n_mb, mask):
     pipe = B.ts_pipeline_create(desc, n_mb)
     streams = [torch.cuda.Stream(), torch.cuda.Stream()]
     copy = torch.cuda.Stream()
+    delta_stream = torch.cuda.Stream()
+    dstride = B.ts_pipeline_kv_delta_stride(desc, per)
+    assert dstride >= per * 2 * s.nkv * s.d * 2 and dstride % 256 == 0
+    delta_dev = torch.zeros(dstride * n_mb, dtype=torch.uint8, device=DEV)
+    delta_host = torch.zeros(dstride * n_mb, dtype=torch.uint8).pin_memory()
     torch.cuda.synchronize()
     try:
         for rep in range(3):       # later repetitions reuse staging slots and workspace halves; the last coalesces sends
+            # the KV delta is replicated in the background from the second repetition on
+            if rep >= 1:
+                B.ts_pipeline_set_kv_delta(pipe, delta_stream, delta_dev, delta_host)
+                delta_host.zero_()
             mbs = [B.make_io({k: v.clone() if k in ("kcache", "vcache") else v for k, v in ios_dev[i].items()},
                              outs[i], per, per) for i in range(n_mb)]
             keep = mbs  # noqa: F841  (cloned caches are referenced only through raw pointers)
@@ -202,8 +211,20 @@ def _pipeline_case(B, wl, weights, io, n_mb, mask):
             host.zero_()
             B.ts_pipeline_step(pipe, wts, mbs, streams, copy, mask, staging, host, ws,
                                copy_mode=B.TS_PIPE_COPY_COALESCED if rep == 2 else B.TS_PIPE_COPY_SIDE_STREAM)
-            for st in streams + [copy]:
+            for st in streams + [copy, delta_stream]:
                 st.synchronize()
+            if rep >= 1:
+                # slot i = for every token its new K row then its new V row, exactly what the cache holds at its position
+                for i in range(n_mb):
+                    c = caches[i]
+                    idx_s = c["seq_id"].long()
+                    idx_p = c["pos"].long()
+                    k_new = c["kcache"][idx_s, :, idx_p, :].reshape(per, -1)
+                    v_new = c["vcache"][idx_s, :, idx_p, :].reshape(per, -1)
+                    want = torch.cat([k_new, v_new], dim=1).contiguous().view(torch.uint8).reshape(-1).cpu()
+                    got = delta_host[i * dstride:i * dstride + want.numel()]
+                    assert torch.equal(got, want), f"micro-batch {i}: KV delta differs from the appended cache rows"
+                    assert torch.equal(delta_dev[i * dstride:i * dstride + want.numel()].cpu(), want)
             for i in range(n_mb):
                 assert torch.equal(outs[i], singles[i][0]), f"micro-batch {i}: output differs from the single-stream layer"
                 assert torch.equal(caches[i]["kcache"], singles[i][2])
