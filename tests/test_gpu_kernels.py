@@ -163,6 +163,8 @@ DECODE_CASES = [
     (64, 8, 128, [700, 33, 4096]),
     (8, 8, 128, [513, 64]),
     (16, 1, 64, [300]),
+    (16, 2, 128, [9000, 300, 4097]),     # up to five chunks per sequence: partials + merge kernel
+    (8, 1, 128, [140001]),               # one long sequence: 68 chunks, offsets beyond 2^24 elements
 ]
 
 

@@ -256,6 +256,18 @@ def test_pipeline_step_matches_single_stream_and_oracle(B, mask):
             assert_close(got, ref, f"micro-batch {i} boundary stream")
 
 
+def test_small_layer_long_contexts_merge_inside_the_attention_launch(B):
+    """Sequences of five, three, two and one chunks in one call: the layer takes the attention path that
+    combines the chunks in the same launch (last chunk to arrive), and must run it twice in a row with the
+    same workspace (the arrival counters are re-armed by the kernel and zeroed by the first norm)."""
+    wl = WL.scaled(WL.CONFIGS["tiny"], B=4)
+    weights, io, lens = WL.build(wl, seed=21, ctx_lens=[9000, 4097, 2300, 100])
+    ref = oracle_layer(wl, weights, io)
+    for rep in range(2):
+        got = run_layer(B, wl, weights, io)
+        compare_layer(got, ref, O.BOUNDARY_ORDER_DENSE)
+
+
 @pytest.mark.parametrize("moe", [False, True])
 def test_layer_forward_replays_from_a_hip_graph(B, moe):
     """The layer enqueues kernels only (no allocation, no memset, no host synchronisation), so it can be
