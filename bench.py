@@ -95,14 +95,14 @@ def measured_traffic(workload, launch, step):
 
 
 FAMILY_OF_LAUNCH = {
-    "rmsnorm": "rmsnorm", "gemm_skinny": "gemm", "gemm_tiled": "gemm", "gemm_mfma256": "gemm", "splitk_reduce": None, "rope": "rope",
+    "rmsnorm": "rmsnorm", "gemm_skinny": "gemm", "gemm_tiled": "gemm", "gemm_mfma256": "gemm", "gemm_mfma256_glu": "gemm", "splitk_reduce": None, "rope": "rope",
     "attn_decode_split": "attn_decode", "attn_decode_merge": None, "attn_prefill": "attn_prefill",
     "swiglu": "swiglu", "moe_topk": "moe_route", "moe_group": None, "moe_invert": None, "moe_combine": "moe_combine",
     "copy16": None,
 }
 
 
-NODE_OF_STEP = {"rmsnorm1": 0, "qkv": 1, "rope+append": 1, "attention": 2, "o": 3, "rmsnorm2": 4, "gate_up": 5, "swiglu": 6,
+NODE_OF_STEP = {"gate_up+swiglu": 5, "rmsnorm1": 0, "qkv": 1, "rope+append": 1, "attention": 2, "o": 3, "rmsnorm2": 4, "gate_up": 5, "swiglu": 6,
                 "down": 7, "router": 5, "route": 5, "expert gate_up": 5, "expert down": 7, "combine": 8}
 # Second GPU types of the planner demonstration: dense bf16 TFLOP/s and HBM GB/s as the paper's Table 1 lists them.
 MODELLED_GPUS = {"L40S-like": (366.5, 864.0), "H100-like": (989.0, 3350.0)}
@@ -129,7 +129,8 @@ def plan_section(B, wl, desc, kernels, n_layers=4, link_GBps=25.0, link_latency_
            "link": {"GBps": link_GBps, "latency_us": link_latency_s * 1e6}, "edges_per_layer": len(edges) // n_layers}
     roof = lambda i, tf, gb: max(flops[i] / (tf * 1e12), nbytes[i] / (gb * 1e9))
     for gname, (tf, gb) in MODELLED_GPUS.items():
-        t1 = [t0[i] * roof(i, tf, gb) / roof(i, MFMA_BF16_PEAK_TFLOPS, HBM_PEAK_GBS) for i in range(nb)]
+        t1 = [t0[i] * roof(i, tf, gb) / roof(i, MFMA_BF16_PEAK_TFLOPS, HBM_PEAK_GBS) if t0[i] > 0 else 0.0
+              for i in range(nb)]
         t = [[t0[k % nb], t1[k % nb]] for k in range(nb * n_layers)]
         bw = [[float("inf"), link_GBps * 1e9], [link_GBps * 1e9, float("inf")]]
         lat = [[0.0, link_latency_s], [link_latency_s, 0.0]]
@@ -330,6 +331,12 @@ def main():
         if fam is not None and mi < len(models) and models[mi][0] == fam:
             _, label, nbytes, flops = models[mi]
             mi += 1
+            if n.endswith("_glu") and mi < len(models) and models[mi][0] == "swiglu":
+                # projection with the activation in its epilogue: the gate/up tensor is written once and not
+                # read back, the activation is written once
+                label = label + "+swiglu"
+                nbytes += models[mi][2] // 3
+                mi += 1
             entry.update({"step": label, "algo_bytes": int(nbytes), "GBps": round(nbytes / (ms * 1e-3) / 1e9, 1),
                           "hbm_frac": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)})
             if flops:

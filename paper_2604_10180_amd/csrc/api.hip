@@ -220,9 +220,15 @@ int layer_forward_impl(const ts_layer_desc& d, const ts_layer_weights& w, const 
   TS_STEP(launch_rmsnorm(x2, w.gamma2, h2, T, d.H, d.eps, s));
   TS_STEP(hook(TS_B_H2, h2));
   if (d.E == 0) {
-    TS_STEP(launch_gemm(h2, w.w_gate_up, nullptr, gate_up, false, T, 2 * d.F, d.H, scratch, p.scratch_bytes, s));
-    TS_STEP(hook(TS_B_GATE_UP, gate_up));
-    TS_STEP(launch_swiglu(gate_up, act, T, d.F, s));
+    if (gemm_mfma256_glu_supported(T, d.F, d.H)) {
+      // MFMA-bound sizes: the activation is applied in the projection's epilogue (both tensors are still written)
+      TS_STEP(launch_gemm_mfma256_glu(h2, w.w_gate_up, gate_up, act, T, d.F, d.H, s));
+      TS_STEP(hook(TS_B_GATE_UP, gate_up));
+    } else {
+      TS_STEP(launch_gemm(h2, w.w_gate_up, nullptr, gate_up, false, T, 2 * d.F, d.H, scratch, p.scratch_bytes, s));
+      TS_STEP(hook(TS_B_GATE_UP, gate_up));
+      TS_STEP(launch_swiglu(gate_up, act, T, d.F, s));
+    }
     TS_STEP(hook(TS_B_ACT, act));
     TS_STEP(launch_gemm(act, w.w_down, x2, io.out, false, T, d.H, d.F, scratch, p.scratch_bytes, s));
     TS_STEP(hook(TS_B_OUT_DENSE, io.out));

@@ -140,6 +140,11 @@ size_t gemm_workspace_bytes(int M, int N, int K);
 int launch_gemm(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, void* C, bool f32out, int M, int N,
                 int K, void* ws, size_t ws_bytes, hipStream_t s);
 bool gemm_mfma256_supported(int M, int N, int K);
+// gate/up projection with SwiGLU in the epilogue (W = F gate rows then F up rows): writes gate_up [M, 2F] and
+// act [M, F] = silu(gate) * up computed from the rounded gate_up values
+bool gemm_mfma256_glu_supported(int M, int F, int K);
+int launch_gemm_mfma256_glu(const ts_bf16* A, const ts_bf16* W, ts_bf16* gate_up, ts_bf16* act, int M, int F, int K,
+                            hipStream_t s);
 int launch_gemm_mfma256(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, ts_bf16* C, int M, int N, int K,
                         hipStream_t s);
 int launch_moe_gemm(const ts_bf16* A, const int32_t* row_map, int row_div, const ts_bf16* W,

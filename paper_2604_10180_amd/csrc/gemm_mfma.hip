@@ -48,10 +48,14 @@ __device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70);
 
 }  // namespace
 
-__global__ __launch_bounds__(512) void gemm_mfma256_kernel(const ts_bf16* __restrict__ A, const ts_bf16* __restrict__ W,
-                                                           const ts_bf16* __restrict__ residual,
-                                                           ts_bf16* __restrict__ C, int M, int N, int K, int tiles_m,
-                                                           int tiles_n) {
+// GLU = true is the gate/up projection of a SwiGLU MLP with the activation applied in the epilogue: W holds F
+// gate rows followed by F up rows (N = 2F); a tile then covers 128 gate columns and the 128 up columns of
+// the same hidden units, writes both to C as usual and silu(gate) * up, computed from the bf16-rounded values
+// exactly as the stand-alone kernel does, to act [M, F].  Requires F % 128 == 0; no residual.
+template <bool GLU>
+__device__ __forceinline__ void gemm_mfma256_body(const ts_bf16* __restrict__ A, const ts_bf16* __restrict__ W,
+                                                  const ts_bf16* __restrict__ residual, ts_bf16* __restrict__ C, int M,
+                                                  int N, int K, int tiles_m, int tiles_n, ts_bf16* __restrict__ act) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int r32 = lane & 31, g = lane >> 5;
@@ -69,7 +73,8 @@ __global__ __launch_bounds__(512) void gemm_mfma256_kernel(const ts_bf16* __rest
   const int first_m = (lid / per_group) * GM;
   const int gsz = min(GM, tiles_m - first_m);
   const int tile_m = first_m + (lid % per_group) % gsz, tile_n = (lid % per_group) / gsz;
-  const int mb = tile_m * kTile, nb = tile_n * kTile;
+  const int F = N >> 1;                                   // GLU only
+  const int mb = tile_m * kTile, nb = tile_n * (GLU ? kTile / 2 : kTile);
 
   // ---- global -> LDS assignment: load q of wave w fills LDS rows (q*8 + w)*8 .. +8 of a tile;
   // lane i lands at 16 i inside that 1 KiB, i.e. row i/8, physical chunk i%8.
@@ -81,7 +86,9 @@ __global__ __launch_bounds__(512) void gemm_mfma256_kernel(const ts_bf16* __rest
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const int R = q * 64 + wave * 8 + lrow;
-    woff[q] = (uint32_t)min(R, N - 1 - nb) * (uint32_t)K * 2u + cl * 16;
+    // GLU: tile rows 128..255 are the up rows of the same 128 hidden units
+    const int wr = GLU ? (R < 128 ? R : F + R - 128) : min(R, N - 1 - nb);
+    woff[q] = (uint32_t)wr * (uint32_t)K * 2u + cl * 16;
     aoff[q] = (uint32_t)min(R, M - 1 - mb) * (uint32_t)K * 2u + cl * 16;
   }
   // load pair h (0..3) of a K step: one W and one A instruction of this wave
@@ -225,16 +232,71 @@ __global__ __launch_bounds__(512) void gemm_mfma256_kernel(const ts_bf16* __rest
   for (int p = 0; p < 16; ++p) {
     const int m = p * 16 + (tid >> 5), pc = tid & 31;
     const int ch = pc ^ (m & 15);
-    const int gm = mb + m, gn = nb + ch * 8;
+    const int gm = mb + m;
+    const int gn = GLU ? (ch < 16 ? nb + ch * 8 : F + nb + (ch - 16) * 8) : nb + ch * 8;
     uint4 v = *reinterpret_cast<const uint4*>(image_row(m) + pc * 16);
     if (m & 16) v = swap_halves(v);
     if (gm < M && gn < N) stg16(C + (size_t)gm * N + gn, v);
   }
+  if (GLU) {
+    // act[m, nb + 8c .. +8) = silu(gate) * up from image chunks c and 16 + c of row m (the swizzle only
+    // permutes the low four bits of the chunk index, so the pair sits at pc and 16 + pc)
+#pragma unroll 4
+    for (int p = 0; p < 8; ++p) {
+      const int m = p * 32 + (tid >> 4), c = tid & 15;
+      const int pc = c ^ (m & 15);
+      U4 gv, uv, o;
+      gv.u = *reinterpret_cast<const uint4*>(image_row(m) + pc * 16);
+      uv.u = *reinterpret_cast<const uint4*>(image_row(m) + (16 + pc) * 16);
+      if (m & 16) {
+        gv.u = swap_halves(gv.u);
+        uv.u = swap_halves(uv.u);
+      }
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const float g0 = bf_lo(gv.w[j]), g1 = bf_hi(gv.w[j]);
+        const float a0 = g0 / (1.0f + __expf(-g0)) * bf_lo(uv.w[j]);
+        const float a1 = g1 / (1.0f + __expf(-g1)) * bf_hi(uv.w[j]);
+        o.w[j] = pack_bf16(a0, a1);
+      }
+      if (mb + m < M) stg16(act + (size_t)(mb + m) * F + nb + c * 8, o.u);
+    }
+  }
+}
+
+__global__ __launch_bounds__(512) void gemm_mfma256_kernel(const ts_bf16* __restrict__ A, const ts_bf16* __restrict__ W,
+                                                           const ts_bf16* __restrict__ residual,
+                                                           ts_bf16* __restrict__ C, int M, int N, int K, int tiles_m,
+                                                           int tiles_n) {
+  gemm_mfma256_body<false>(A, W, residual, C, M, N, K, tiles_m, tiles_n, nullptr);
+}
+
+__global__ __launch_bounds__(512) void gemm_mfma256_glu_kernel(const ts_bf16* __restrict__ A,
+                                                               const ts_bf16* __restrict__ W,
+                                                               ts_bf16* __restrict__ gate_up,
+                                                               ts_bf16* __restrict__ act, int M, int N, int K,
+                                                               int tiles_m, int tiles_n) {
+  gemm_mfma256_body<true>(A, W, nullptr, gate_up, M, N, K, tiles_m, tiles_n, act);
 }
 
 bool gemm_mfma256_supported(int M, int N, int K) {
   // full 64-wide K steps, 16-byte output chunks, tile-relative byte offsets within 32 bits
   return K >= kBK && K % kBK == 0 && N % 8 == 0 && N >= 8 && (long)K * 2 * kTile < (1L << 31);
+}
+
+bool gemm_mfma256_glu_supported(int M, int F, int K) {
+  // whole 128-column halves, byte offsets of the up rows relative to the tile within 32 bits, enough tiles
+  return K >= kBK && K % kBK == 0 && F >= 128 && F % 128 == 0 && ((long)F + 256) * K * 2 < (1L << 32) &&
+         (long)cdiv(M, kTile) * (F / 128) >= 192;
+}
+
+int launch_gemm_mfma256_glu(const ts_bf16* A, const ts_bf16* W, ts_bf16* gate_up, ts_bf16* act, int M, int F, int K,
+                            hipStream_t s) {
+  const int tiles_m = cdiv(M, kTile), tiles_n = F / 128;
+  TS_LAUNCH("gemm_mfma256_glu", gemm_mfma256_glu_kernel, dim3(tiles_m * tiles_n), dim3(512), 0, s, A, W, gate_up, act, M,
+            2 * F, K, tiles_m, tiles_n);
+  TS_LAUNCH_CHECK("gemm_mfma256_glu");
+  return TS_OK;
 }
 
 int launch_gemm_mfma256(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, ts_bf16* C, int M, int N, int K,

@@ -127,6 +127,27 @@ def test_small_prefill_layer_then_decode(B):
     compare_layer(got_d, ref_d, O.BOUNDARY_ORDER_DENSE)
 
 
+def test_prefill_layer_with_the_activation_in_the_projection_epilogue(B):
+    """2048 tokens x F = 3072 is the smallest shape whose gate/up projection takes the 256 x 256 MFMA kernel
+    with SwiGLU applied in its epilogue: gate_up and act must both be what the separate kernels produce."""
+    shape = WL.LayerShape(H=512, nq=8, nkv=2, d=64, F=3072)
+    wl = WL.Workload("glu", shape, "prefill", B=3, seq_tokens=0)
+    gen = torch.Generator().manual_seed(13)
+    weights = WL.make_weights(shape, gen)
+    seqs = [1000, 24, 1024]
+    io = WL.make_prefill_io(shape, seqs, gen, Lcap=1024)
+    got = run_layer(B, wl, weights, io)
+    ref = oracle_layer(wl, weights, io)
+    compare_layer(got, ref, O.BOUNDARY_ORDER_DENSE)
+    # act is exactly silu(gate) * up of the bf16 gate_up the kernel wrote (fp32 arithmetic, one rounding)
+    gu = torch.tensor(got["gate_up"]).reshape(sum(seqs), 2 * shape.F).float()
+    g, u = gu[:, :shape.F], gu[:, shape.F:]
+    want = (g / (1.0 + torch.exp(-g)) * u).to(torch.bfloat16).double().numpy()
+    diff = np.abs(got["act"].reshape(want.shape) - want)
+    tol = np.maximum(np.abs(want) * 2.0 ** -7, 1e-30)          # at most one bf16 ulp (exp is the device's fast one)
+    assert np.all(diff <= tol)
+
+
 def test_small_moe_layer_teacher_forced(B):
     shape = WL.LayerShape(H=512, nq=8, nkv=2, d=64, F=688, E=8, k=2)
     wl = WL.Workload("moe", shape, "decode", B=48)
