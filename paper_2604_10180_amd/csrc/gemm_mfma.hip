@@ -285,9 +285,11 @@ bool gemm_mfma256_supported(int M, int N, int K) {
 }
 
 bool gemm_mfma256_glu_supported(int M, int F, int K) {
-  // whole 128-column halves, byte offsets of the up rows relative to the tile within 32 bits, enough tiles
-  return K >= kBK && K % kBK == 0 && F >= 128 && F % 128 == 0 && ((long)F + 256) * K * 2 < (1L << 32) &&
-         (long)cdiv(M, kTile) * (F / 128) >= 192;
+  // more token rows than the streaming kernel takes and enough 256 x 256 tiles (the conditions under which
+  // the plain projection runs on this kernel), whole 128-column halves, byte offsets of the up rows relative
+  // to the tile within 32 bits
+  return M > 128 && (long)cdiv(M, kTile) * cdiv(2 * F, kTile) >= 192 && K >= kBK && K % kBK == 0 && F >= 128 &&
+         F % 128 == 0 && ((long)F + 256) * K * 2 < (1L << 32);
 }
 
 int launch_gemm_mfma256_glu(const ts_bf16* A, const ts_bf16* W, ts_bf16* gate_up, ts_bf16* act, int M, int F, int K,
