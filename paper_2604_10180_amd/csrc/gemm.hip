@@ -512,7 +512,7 @@ template <int MT, int NT> constexpr int skinny_stages() { return (MT <= 2 && NT 
 
 template <int MT, bool GROUPED>
 void launch_skinny_mt(const SkinnyArgs& a, int NT, dim3 grid, hipStream_t s, int waves = 4) {
-  if constexpr (!GROUPED && MT <= 4) {
+  if constexpr ((!GROUPED && MT <= 4) || (GROUPED && MT >= 4)) {
     if (waves == 7 || waves == 8) {
       auto go = [&](auto nt_c, auto w_c) {
         constexpr int NTc = decltype(nt_c)::value, Wc = decltype(w_c)::value;
@@ -548,8 +548,8 @@ void launch_skinny(const SkinnyArgs& a, int mrows, int NT, dim3 grid, hipStream_
   if (mrows <= 16) launch_skinny_mt<1, GROUPED>(a, NT, grid, s, waves);
   else if (mrows <= 32) launch_skinny_mt<2, GROUPED>(a, NT, grid, s, waves);
   else if (mrows <= 64) launch_skinny_mt<4, GROUPED>(a, NT, grid, s, waves);
-  else if (mrows <= 96) launch_skinny_mt<6, GROUPED>(a, NT, grid, s);
-  else launch_skinny_mt<8, GROUPED>(a, NT, grid, s);
+  else if (mrows <= 96) launch_skinny_mt<6, GROUPED>(a, NT, grid, s, waves);
+  else launch_skinny_mt<8, GROUPED>(a, NT, grid, s, waves);
 }
 
 }  // namespace
@@ -653,14 +653,37 @@ int launch_moe_gemm(const ts_bf16* A, const int32_t* row_map, int row_div, const
   a.A = A; a.row_map = row_map; a.row_div = row_div; a.W = W; a.offsets = offsets; a.residual = nullptr; a.C = C;
   a.partial = nullptr; a.M = rows; a.N = N; a.K = K; a.kslice = (int)round_up((size_t)K, 128); a.S = 1; a.f32out = 0;
   a.w_group_stride = (long)N * K;
-  const int NT = (cdiv(N, 128) * E >= 448) ? 2 : 1;
-  dim3 grid(cdiv(N, 64 * NT), 1, E);
+  int NT = (cdiv(N, 128) * E >= 448) ? 2 : 1;
   // Row tile: sized for the average expert load; larger experts loop over row blocks.
   const int avg = cdiv(rows, E);
   // (96 rows keep two workgroups per CU and take a 64-row average with its usual spread in one
   // pass: 4.5 TB/s on 8 experts x 64 rows against 3.8 with 128-row tiles and 3.2 with 64-row tiles)
   const int mrows = avg <= 8 ? 16 : (avg <= 20 ? 32 : (avg <= 44 ? 64 : (avg <= 72 ? 96 : 128)));
-  launch_skinny<true>(a, mrows, NT, grid, s);
+  int waves = 4;
+  if (mrows > 32) {
+    // Wider workgroups share one activation slab among more weight rows and keep more loads in flight.  Same
+    // load model as the dense plan (workgroups per CU, activation re-reads), with the measured bonus of the
+    // seven/eight-wave form at equal width.  8 experts x ~64 rows, H = 4096, F = 14336: gate/up 428 -> 363 us
+    // (7 waves x 32 rows), down 211 -> 189 us (8 waves x 16 rows); the other combinations measured worse.
+    auto score = [&](int w, int nt) {
+      const int cols = 16 * w * nt;
+      const long wgs = (long)cdiv(N, cols) * E;
+      const double quant = (double)((wgs + 255) / 256 * 256) / (double)wgs;
+      return quant * (1.0 + 0.35 * mrows / cols) * (w > 4 ? 0.9 : 1.0);
+    };
+    double best = score(4, NT);
+    const int cand[2][2] = {{7, 2}, {8, 1}};
+    for (const auto& c : cand) {
+      const double sc = score(c[0], c[1]);
+      if (sc < best) {
+        best = sc;
+        waves = c[0];
+        NT = c[1];
+      }
+    }
+  }
+  dim3 grid(cdiv(N, 16 * waves * NT), 1, E);
+  launch_skinny<true>(a, mrows, NT, grid, s, waves);
   TS_LAUNCH_CHECK("moe_gemm");
   return TS_OK;
 }
