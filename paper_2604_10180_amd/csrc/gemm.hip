@@ -464,26 +464,27 @@ SkinnyPlan plan_skinny(int M, int N, int K) {
       if (p.S > 16) p.S = 16;
     }
   }
-  // 17..64 token rows: also consider seven- and eight-wave workgroups (112 / 128 weight rows).  The model
+  // Up to 64 token rows: also consider seven- and eight-wave workgroups (112 / 128 weight rows).  The model
   // behind the choice: the most loaded CU runs ceil(workgroups / 256) of them, a workgroup's traffic is its
   // weight slice plus the activation rows it re-reads from L2 (about a third as expensive per byte), and
   // every K slice adds partial-sum traffic.  Measured with it: 8B shapes at 64 rows, gate/up 58 -> 49 us,
   // down 34 -> 31 us, qkv 20 -> 18.6 us; 70B shapes at 32 rows, qkv 46 -> 36 us, o 40 -> 31 us (8B decode
-  // layer 0.2415 -> 0.2283 ms, 70B layer 0.763 -> 0.748 ms, same box).
-  if (M > 16 && M <= 64 && p.NT == 1) {   // (very wide outputs already stream at the cap with 128-row workgroups)
-    const int rows = M <= 32 ? 32 : 64;
+  // layer 0.2415 -> 0.2283 ms, 70B layer 0.763 -> 0.748 ms, same box); at 8 rows qkv 42 -> 34 us, o 39 -> 29 us.
+  if (M <= 64 && p.NT == 1) {   // (very wide outputs already stream at the cap with 128-row workgroups)
+    const int rows = M <= 16 ? 16 : (M <= 32 ? 32 : 64);
     auto score = [&](int waves, int NT, int S) {
       const int cols = 16 * waves * NT;
       const long wgs = (long)cdiv(N, cols) * S;
       const double quant = (double)((wgs + 255) / 256 * 256) / (double)wgs;
-      return quant * (1.0 + 0.35 * rows / cols) * (1.0 + 0.02 * S);
+      // (at equal width the seven/eight-wave form measured about a tenth faster: more loads in flight per slab)
+      return quant * (1.0 + 0.35 * rows / cols) * (1.0 + 0.02 * S) * (waves > 4 ? 0.9 : 1.0);
     };
     const double legacy = score(4, p.NT, p.S);
     double best = legacy;
     int maxs = K / 512;
     maxs = maxs < 1 ? 1 : (maxs > 16 ? 16 : maxs);
     for (int waves : {7, 8})
-      for (int S = 1; S <= maxs; ++S) {
+      for (int S = 1; S <= maxs && N >= 16 * waves; ++S) {
         const double sc = score(waves, 1, S);
         if (sc < 0.95 * legacy && sc < best) {
           best = sc;
