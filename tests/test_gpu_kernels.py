@@ -268,7 +268,9 @@ def test_moe_route_shapes(B, T, E, k):
     assert np.allclose(outs[1].cpu().numpy(), w, atol=2e-7)
 
 
-@pytest.mark.parametrize("T,E,k,H,N", [(40, 4, 2, 256, 688), (256, 8, 2, 512, 1024), (9, 8, 2, 128, 64), (600, 3, 1, 64, 130)])
+@pytest.mark.parametrize("T,E,k,H,N", [(40, 4, 2, 256, 688), (256, 8, 2, 512, 1024), (9, 8, 2, 128, 64), (600, 3, 1, 64, 130),
+                                       (256, 8, 2, 256, 7160),     # seven-wave x 32-row expert workgroups, ragged last tile
+                                       (256, 8, 2, 384, 4090)])    # eight-wave x 16-row expert workgroups, ragged last tile
 def test_moe_gemm_and_combine(B, T, E, k, H, N):
     g = gen(T + E + N)
     A = WL.randn_bf16(g, T, H)
