@@ -15,13 +15,13 @@
 // one whole 128-byte row (fully coalesced), and an MFMA operand read (32 rows x one logical
 // chunk) touches every bank group equally.
 //
-// What bounds it: not the matrix cores.  With the ring loads removed the same loop runs at 1.81 PFLOP/s
-// (the clock the chip sustains under this load); with the loads issued but never waited for it runs
-// exactly as fast as the real kernel (1.18), and with every load hitting L2 at 1.28.  A CU sustains about
-// 64 outstanding 128-byte requests towards L2, which at the L2 round trip is 20-23 bytes per clock per CU,
-// also when only 32 CUs run; a 256 x 256 tile needs 32 bytes per clock per CU at the MFMA peak.  A
-// four-wave variant (128 x 128 per wave, one third less LDS traffic, barrier hidden behind the last
-// k-step) measured 7 % slower: the loads, not the LDS reads or the barrier, set the time.
+// What bounds it: not the matrix cores alone.  With the ring loads removed the same loop runs at 1.81 PFLOP/s;
+// with the loads issued but never waited for it runs exactly as fast as the real kernel (1.18), and with
+// every load hitting L2 at 1.28, although a bare global->LDS loop moves twice the bytes per clock that this
+// kernel needs.  With the loads the chip holds 1.81 GHz instead of 2.19, and per K step the workgroup's
+// 192 KB of fragment reads share the LDS with 64 KB of incoming tile data: 256 KB per 2048 MFMA clocks is
+// the LDS's nominal 128 B/clk.  A four-wave variant (128 x 128 per wave, a third less LDS traffic, barrier
+// hidden behind the last k-step) measured 7 % slower: one wave per SIMD has nothing to issue at the barrier.
 //
 // Epilogue: the residual tile is staged into LDS coalesced, each lane adds its accumulators to
 // its own slots in fp32 and rounds once, and the bf16 tile leaves as full 512-byte row
