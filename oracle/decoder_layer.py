@@ -11,8 +11,8 @@ matrix products bandwidth-bound, tiled prefill attention compute-bound); it
 prints no formula for them.  The definitions used here are therefore the
 standard Llama/Mixtral-style ones that the benchmark configurations name
 (RMSNorm, y = A W^T projections, rotate-half RoPE, GQA softmax attention over
-a contiguous KV cache, SwiGLU, top-k softmax routing); every reading taken is
-listed in DESIGN.md ("Readings").  `np.matmul` serves as a library step for the
+a contiguous KV cache, SwiGLU, top-k softmax routing); each function below
+states the reading it takes.  `np.matmul` serves as a library step for the
 dense contractions; there is no blocking, fusion or reordering here.
 
 Arithmetic: float64 everywhere.  Inputs are bf16-representable values widened

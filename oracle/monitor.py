@@ -10,7 +10,7 @@ the requests that finished inside the window are formed; their ratio L_req / L_e
 queueing pressure; a ratio above the threshold beta selects the throughput-oriented policy, a ratio
 at or below it the latency-oriented one.  Defaults of Sec. 5.4: W = 0.3 s, beta = 1.5.
 
-Readings taken (the paper leaves them open; listed in the design doc):
+Readings taken (the paper leaves them open):
   M1  a request belongs to the window in which it completes; window n is [n W, (n+1) W).
   M2  the indicator is the ratio of the two window means, not the mean of per-request ratios.
   M3  a window without completions carries no information: the policy stays.

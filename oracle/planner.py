@@ -21,7 +21,7 @@ What it is:
   objective min sum t x + sum of c over cut edges) and minimised by
   enumerating every placement.  Exponential on purpose.
 
-Readings taken (the paper leaves them open; listed in the design doc):
+Readings taken (the paper leaves them open):
   P1  an access is a byte range [addr, addr + extent) plus the number of bytes
       actually touched inside it (`bytes <= extent`; the analyzer of Sec. 3.1
       keeps a [min, max] hull per instruction).  The bytes that flow along a
