@@ -97,7 +97,7 @@ def measured_traffic(workload, launch, step):
 FAMILY_OF_LAUNCH = {
     "rmsnorm": "rmsnorm", "gemm_skinny": "gemm", "gemm_tiled": "gemm", "gemm_mfma256": "gemm", "gemm_mfma256_glu": "gemm", "splitk_reduce": None, "rope": "rope",
     "attn_decode_split": "attn_decode", "attn_decode_merge": None, "attn_prefill": "attn_prefill",
-    "swiglu": "swiglu", "moe_topk": "moe_route", "moe_group": None, "moe_invert": None, "moe_combine": "moe_combine",
+    "swiglu": "swiglu", "moe_router": "gemm", "moe_topk": "moe_route", "moe_group": None, "moe_invert": None, "moe_combine": "moe_combine",
     "copy16": None,
 }
 

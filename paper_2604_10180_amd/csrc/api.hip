@@ -242,7 +242,10 @@ int layer_forward_impl(const ts_layer_desc& d, const ts_layer_weights& w, const 
     int32_t* inv = reinterpret_cast<int32_t*>(ws + p.inv);
     ts_bf16* y = reinterpret_cast<ts_bf16*>(ws + p.y);
     const int rows = T * d.k;
-    TS_STEP(launch_gemm(h2, w.w_router, nullptr, logits, true, T, d.E, d.H, scratch, p.scratch_bytes, s));
+    if (moe_router_supported(d.E, d.H))
+      TS_STEP(launch_moe_router(h2, w.w_router, logits, T, d.E, d.H, s));
+    else
+      TS_STEP(launch_gemm(h2, w.w_router, nullptr, logits, true, T, d.E, d.H, scratch, p.scratch_bytes, s));
     TS_STEP(launch_moe_route(logits, T, d.E, d.k, tidx, tw, counts, offs, perm, s));
     TS_STEP(launch_moe_gemm(h2, perm, d.k, w.w_gate_up, offs, gate_up, rows, d.E, 2 * d.F, d.H, s));
     TS_STEP(hook(TS_B_GATE_UP, gate_up));

@@ -160,6 +160,9 @@ int launch_attention_prefill(const ts_bf16* q, const ts_bf16* k, const ts_bf16* 
                              const int32_t* cu, ts_bf16* out, int S, int T, int max_seqlen, int nq, int nkv, int d,
                              float scale, int causal, hipStream_t s);
 
+// router projection for up to 16 experts (one wave per token); larger routers go through launch_gemm
+bool moe_router_supported(int E, int H);
+int launch_moe_router(const ts_bf16* h, const ts_bf16* w_router, float* logits, int T, int E, int H, hipStream_t s);
 int launch_moe_route(const float* logits, int T, int E, int k, int32_t* idx, float* w, int32_t* counts,
                      int32_t* offsets, int32_t* perm, hipStream_t s);
 int launch_moe_combine(const ts_bf16* y, const int32_t* perm, const float* w, const ts_bf16* residual, ts_bf16* out,

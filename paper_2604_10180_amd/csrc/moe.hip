@@ -3,6 +3,58 @@
 
 namespace ts {
 
+// Router logits for a handful of experts (E <= 16): logits[t, e] = h[t, :] . Wr[e, :] in fp32.  One workgroup
+// per token; a thread takes every 256th 16-byte chunk of the row against the same chunk of all E router rows
+// (64 KB at E = 8, H = 4096: served by the caches); the E sums are reduced across the wave, then across the
+// four waves through LDS in wave order.  As a GEMM this is a single 8-column tile, i.e. eight workgroups
+// after splitting K.
+template <int EMAX>
+__global__ __launch_bounds__(256) void moe_router_kernel(const uint4* __restrict__ h, const uint4* __restrict__ wr,
+                                                         float* __restrict__ logits, int T, int E, int H8) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int t = blockIdx.x;
+  float acc[EMAX];
+#pragma unroll
+  for (int e = 0; e < EMAX; ++e) acc[e] = 0.f;
+  const uint4* row = h + (size_t)t * H8;
+  for (int c = tid; c < H8; c += 256) {
+    U4 x;
+    x.u = row[c];
+    float xf[8];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) { xf[2 * j] = bf_lo(x.w[j]); xf[2 * j + 1] = bf_hi(x.w[j]); }
+#pragma unroll
+    for (int e = 0; e < EMAX; ++e) {
+      if (e < E) {
+        U4 w;
+        w.u = wr[(size_t)e * H8 + c];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[e] += xf[2 * j] * bf_lo(w.w[j]) + xf[2 * j + 1] * bf_hi(w.w[j]);
+      }
+    }
+  }
+  __shared__ float part[4][EMAX];
+#pragma unroll
+  for (int e = 0; e < EMAX; ++e) {
+    const float v = wave_sum(acc[e]);
+    if (lane == 0) part[wave][e] = v;
+  }
+  __syncthreads();
+  if (tid < E) logits[(size_t)t * E + tid] = ((part[0][tid] + part[1][tid]) + part[2][tid]) + part[3][tid];
+}
+
+bool moe_router_supported(int E, int H) { return E >= 1 && E <= 16 && H % 8 == 0; }
+
+int launch_moe_router(const ts_bf16* h, const ts_bf16* w_router, float* logits, int T, int E, int H, hipStream_t s) {
+  if (T == 0) return TS_OK;
+  const uint4* hp = reinterpret_cast<const uint4*>(h);
+  const uint4* wp = reinterpret_cast<const uint4*>(w_router);
+  if (E <= 8) TS_LAUNCH("moe_router", moe_router_kernel<8>, dim3(T), dim3(256), 0, s, hp, wp, logits, T, E, H / 8);
+  else TS_LAUNCH("moe_router", moe_router_kernel<16>, dim3(T), dim3(256), 0, s, hp, wp, logits, T, E, H / 8);
+  TS_LAUNCH_CHECK("moe_router");
+  return TS_OK;
+}
+
 // One thread per token: k rounds of "largest remaining logit, lowest index on ties".
 __global__ __launch_bounds__(256) void moe_topk_kernel(const float* __restrict__ logits, int T, int E, int k,
                                                        int32_t* __restrict__ idx, float* __restrict__ w) {
