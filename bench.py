@@ -154,7 +154,7 @@ def plan_section(B, wl, desc, kernels, n_layers=4, link_GBps=25.0, link_latency_
     return out
 
 
-def time_pipeline(B, torch, wl, desc, dev_set, io_cpu, dev, steps, warmup):
+def time_pipeline(B, torch, wl, desc, dev_set, io_cpu, dev, steps, warmup, extra_masks=None):
     """ts_pipeline_step over wl.n_micro micro-batches (index order), three ways: no boundary
     copies, all boundaries copied on the side stream (one send per boundary, or coalesced into three
     sends per layer), all boundaries copied on the compute streams.  Overlap holds when the
@@ -181,8 +181,12 @@ def time_pipeline(B, torch, wl, desc, dev_set, io_cpu, dev, steps, warmup):
     copy = torch.cuda.Stream()
     out = {"micro_batches": n_mb, "sequences_per_micro_batch": per, "boundary_bytes_per_step": int(stride * n_mb)}
     try:
-        for name, mask, mode in (("no_copies", 0, B.TS_PIPE_COPY_SIDE_STREAM), ("side_stream", full, B.TS_PIPE_COPY_SIDE_STREAM),
-                                 ("coalesced", full, B.TS_PIPE_COPY_COALESCED), ("serialised", full, B.TS_PIPE_COPY_SERIALISED)):
+        cases = [("no_copies", 0, B.TS_PIPE_COPY_SIDE_STREAM), ("side_stream", full, B.TS_PIPE_COPY_SIDE_STREAM),
+                 ("coalesced", full, B.TS_PIPE_COPY_COALESCED), ("serialised", full, B.TS_PIPE_COPY_SERIALISED)]
+        # only the cut edges of a planned placement (the slot layout is sized for the full mask, so any subset fits)
+        for label, m in (extra_masks or {}).items():
+            cases.append((f"planned_{label}", m & full, B.TS_PIPE_COPY_SIDE_STREAM))
+        for name, mask, mode in cases:
             def one():
                 B.ts_pipeline_step(pipe, wts, mbs, streams, copy, mask, staging, host, ws, copy_mode=mode)
             for _ in range(warmup):
@@ -371,11 +375,18 @@ def main():
         "kernels": kernels,
     }
 
-    if args.pipeline and wl.mode == "decode" and wl.n_micro > 1:
-        result["pipeline"] = time_pipeline(B, torch, wl, desc, sets[0], io, dev, max(5, args.steps // 2), args.warmup)
-
     if args.plan:
         result["plan"] = plan_section(B, wl, desc, kernels)
+
+    if args.pipeline and wl.mode == "decode" and wl.n_micro > 1:
+        planned = {}
+        if args.plan:
+            for gname in MODELLED_GPUS:
+                m = result["plan"][gname]["throughput"]["boundary_mask_layer0"]
+                if m:
+                    planned[f"{gname}_mask_{m}"] = m
+        result["pipeline"] = time_pipeline(B, torch, wl, desc, sets[0], io, dev, max(5, args.steps // 2), args.warmup,
+                                           planned)
 
     if args.graph:
         side = torch.cuda.Stream()
