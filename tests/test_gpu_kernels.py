@@ -135,6 +135,27 @@ def test_gemm(B, M, N, K, with_res):
     assert_close(Cd, ref, f"gemm {M}x{N}x{K} res={with_res}")
 
 
+def test_gemm_seeded_random_shapes(B):
+    """Sixty seeded shapes across the dispatch rules (row tiles, seven/eight-wave workgroups, split K, tails in
+    every dimension): none may fall between two kernels' assumptions."""
+    rng = np.random.default_rng(2024)
+    for case in range(60):
+        M = int(rng.choice([1, 3, 8, 16, 17, 31, 33, 64, 65, 100, 128, 129, 200]))
+        N = int(rng.integers(1, 1600)) * 2
+        K = int(rng.integers(1, 700)) * 8
+        if case % 5 == 0:
+            N, K = int(rng.choice([4096, 6144, 10240, 28672])), int(rng.choice([512, 1024, 2048]))
+        g = gen(1000 + case)
+        A = WL.randn_bf16(g, M, K)
+        W = WL.randn_bf16(g, N, K, std=0.05)
+        R = WL.randn_bf16(g, M, N) if case % 2 else None
+        Cd = torch.full((M, N), 7.0, dtype=torch.bfloat16, device=DEV)
+        ws = ws_bytes(B.ts_gemm_workspace_bytes(M, N, K))
+        B.ts_gemm_bf16(dev(A), dev(W), None if R is None else dev(R), Cd, M, N, K, ws)
+        ref = O.gemm(WL.as_f64(A), WL.as_f64(W), None if R is None else WL.as_f64(R))
+        assert_close(Cd, ref, f"case {case}: M={M} N={N} K={K} residual={R is not None}")
+
+
 @pytest.mark.parametrize("M,N,K", [(256, 8, 4096), (5, 8, 256), (200, 64, 512)])
 def test_gemm_f32out(B, M, N, K):
     g = gen(M * N)
