@@ -209,6 +209,32 @@ def test_attention_decode(B, nq, nkv, d, lens):
     assert_close(out, ref, f"decode attention nq={nq} nkv={nkv} d={d} lens={lens}")
 
 
+def test_attention_decode_seeded_random(B):
+    """Twenty seeded cases over head layouts (GQA group 1..16, d 64/128) and length mixes that include empty
+    sequences, one key, block and chunk boundaries."""
+    rng = np.random.default_rng(77)
+    special = [0, 1, 31, 32, 33, 2047, 2048, 2049, 4096, 4225]
+    for case in range(20):
+        d = int(rng.choice([64, 128]))
+        nkv = int(rng.choice([1, 2, 4, 8]))
+        g_ = int(rng.choice([1, 2, 4, 8, 16]))
+        nq = nkv * g_
+        Bs = int(rng.integers(1, 7))
+        lens = [int(rng.choice(special)) if rng.random() < 0.5 else int(rng.integers(0, 5000)) for _ in range(Bs)]
+        Lcap = max(max(lens), 1) + int(rng.integers(0, 40))
+        g = gen(5000 + case)
+        q = WL.randn_bf16(g, Bs, nq, d)
+        kc = WL.randn_bf16(g, Bs, nkv, Lcap, d)
+        vc = WL.randn_bf16(g, Bs, nkv, Lcap, d)
+        sl = torch.tensor(lens, dtype=torch.int32)
+        out = torch.full((Bs, nq, d), 9.0, dtype=torch.bfloat16, device=DEV)
+        ws = ws_bytes(B.ts_attention_decode_workspace_bytes(Bs, nq, nkv, d, Lcap))
+        scale = 1 / math.sqrt(d)
+        B.ts_attention_decode(dev(q), dev(kc), dev(vc), dev(sl), out, Bs, nq, nkv, d, Lcap, scale, ws)
+        ref = O.attention_decode(WL.as_f64(q), WL.as_f32(kc), WL.as_f32(vc), lens, scale)
+        assert_close(out, ref, f"case {case}: nq={nq} nkv={nkv} d={d} lens={lens} Lcap={Lcap}")
+
+
 def test_attention_decode_degenerate(B):
     g = gen(3)
     nq, nkv, d, Lcap = 8, 2, 128, 64
