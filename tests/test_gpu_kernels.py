@@ -281,6 +281,35 @@ def test_attention_prefill(B, nq, nkv, d, seqs, causal):
     assert_close(out, ref, f"prefill attention seqs={seqs} causal={causal}")
 
 
+def test_attention_prefill_seeded_random(B):
+    """Twelve seeded cases: GQA groups 1..8, d 64/128, causal or not, sequence lengths around the 32-query and
+    64-key block edges, empty sequences between others."""
+    rng = np.random.default_rng(99)
+    edges = [0, 1, 31, 32, 33, 63, 64, 65, 127, 128, 129, 255, 257]
+    for case in range(12):
+        d = int(rng.choice([64, 128]))
+        nkv = int(rng.choice([1, 2, 4]))
+        nq = nkv * int(rng.choice([1, 2, 3, 4, 6, 8]))
+        seqs = [int(rng.choice(edges)) if rng.random() < 0.6 else int(rng.integers(1, 600)) for _ in range(int(rng.integers(1, 5)))]
+        if sum(seqs) == 0:
+            seqs.append(70)
+        causal = bool(case % 3)
+        g = gen(7000 + case)
+        T = sum(seqs)
+        nqkv = (nq + 2 * nkv) * d
+        qkv = WL.randn_bf16(g, T, nqkv)
+        cu = torch.tensor(np.concatenate([[0], np.cumsum(seqs)]), dtype=torch.int32)
+        out = torch.full((T, nq, d), 9.0, dtype=torch.bfloat16, device=DEV)
+        qd = dev(qkv)
+        scale = 1 / math.sqrt(d)
+        B.ts_attention_prefill(qd, qd[:, nq * d:], qd[:, (nq + nkv) * d:], nqkv, nqkv, dev(cu), out, len(seqs), T,
+                               max(seqs), nq, nkv, d, scale, causal)
+        x = WL.as_f64(qkv)
+        ref = O.attention_prefill(x[:, : nq * d].reshape(T, nq, d), x[:, nq * d:(nq + nkv) * d].reshape(T, nkv, d),
+                                  x[:, (nq + nkv) * d:].reshape(T, nkv, d), cu.numpy(), scale, causal)
+        assert_close(out, ref, f"case {case}: nq={nq} nkv={nkv} d={d} seqs={seqs} causal={causal}")
+
+
 # ------------------------------------------------------------------ MoE
 def test_moe_route_exact(B):
     g = gen(11)
