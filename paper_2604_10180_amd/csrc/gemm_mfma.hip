@@ -15,13 +15,13 @@
 // one whole 128-byte row (fully coalesced), and an MFMA operand read (32 rows x one logical
 // chunk) touches every bank group equally.
 //
-// What bounds it: not the matrix cores alone.  With the ring loads removed the same loop runs at 1.81 PFLOP/s;
-// with the loads issued but never waited for it runs exactly as fast as the real kernel (1.18), and with
-// every load hitting L2 at 1.28, although a bare global->LDS loop moves twice the bytes per clock that this
-// kernel needs.  With the loads the chip holds 1.81 GHz instead of 2.19, and per K step the workgroup's
-// 192 KB of fragment reads share the LDS with 64 KB of incoming tile data: 256 KB per 2048 MFMA clocks is
-// the LDS's nominal 128 B/clk.  A four-wave variant (128 x 128 per wave, a third less LDS traffic, barrier
-// hidden behind the last k-step) measured 7 % slower: one wave per SIMD has nothing to issue at the barrier.
+// What bounds it (8192 x 28672 x 4096): with random operands the chip is power-managed (1.81 GHz against
+// 2.19 GHz without the ring loads) and every variant with real loads lands at 1.2 PFLOP/s; the vendor library
+// reaches 1.42-1.52 there.  With all-zero operands (full clock) this kernel runs at 1.38, at 1.96 without its
+// loads, 1.70 when every load hits L2 and 1.67 without the ring barrier: the 19 % of the loads that miss L2
+// arrive late and unevenly and the barrier couples all eight waves to the slowest.  Four-wave variants
+// (128 x 128 per wave; also with a four-stage ring of 32-wide K steps and partial vmcnt waits) passed parity
+// and measured 1.08-1.12 on random data.
 //
 // Epilogue: the residual tile is staged into LDS coalesced, each lane adds its accumulators to
 // its own slots in fp32 and rounds once, and the bf16 tile leaves as full 512-byte row
@@ -131,13 +131,14 @@ __device__ __forceinline__ void gemm_mfma256_body(const ts_bf16* __restrict__ A,
       for (int j = 0; j < 2; ++j)
         acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i].b, af[j].b, acc[i][j], 0, 0, 0);
   };
-  auto order = [&]() {   // instruction order of the block just written: (LDS read, MFMA) x 6, MFMA x 2
+  auto order = [&]() {   // instruction order of the block just written: MFMA, (LDS read, MFMA) x 6, MFMA
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
 #pragma unroll
     for (int r = 0; r < 6; ++r) {
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
   };
   auto step = [&](const uint4* cur, uint4* nxt, int knext) {
     const char* st = reinterpret_cast<const char*>(cur);
