@@ -23,15 +23,15 @@ __global__ __launch_bounds__(256) void moe_router_kernel(const uint4* __restrict
     float xf[8];
 #pragma unroll
     for (int j = 0; j < 4; ++j) { xf[2 * j] = bf_lo(x.w[j]); xf[2 * j + 1] = bf_hi(x.w[j]); }
+    // rows past E re-read the last router row (their sums are never stored): no branch, so all loads of a chunk
+    // are in flight together
+    U4 w[EMAX];
 #pragma unroll
-    for (int e = 0; e < EMAX; ++e) {
-      if (e < E) {
-        U4 w;
-        w.u = wr[(size_t)e * H8 + c];
+    for (int e = 0; e < EMAX; ++e) w[e].u = wr[(size_t)(e < E ? e : E - 1) * H8 + c];
 #pragma unroll
-        for (int j = 0; j < 4; ++j) acc[e] += xf[2 * j] * bf_lo(w.w[j]) + xf[2 * j + 1] * bf_hi(w.w[j]);
-      }
-    }
+    for (int e = 0; e < EMAX; ++e)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) acc[e] += xf[2 * j] * bf_lo(w[e].w[j]) + xf[2 * j + 1] * bf_hi(w[e].w[j]);
   }
   __shared__ float part[4][EMAX];
 #pragma unroll
