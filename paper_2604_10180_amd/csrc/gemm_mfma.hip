@@ -3,30 +3,33 @@
 //
 // One workgroup = 8 waves (two per SIMD, so one wave's LDS/global traffic hides behind the
 // other's MFMAs) computes a 256 (n) x 256 (m) tile of C; wave (wn, wm) owns 128 n x 64 m as
-// 4 x 2 accumulators of the 32x32x16 MFMA.  K advances 64 per step through a two-stage LDS
-// ring that is filled by direct global->LDS loads (no VGPR round trip, no LDS store
-// instructions).
+// 8 x 4 accumulators of the 16x16x32 MFMA (on random operands a register-resident loop of this
+// shape sustains 2.05 PFLOP/s under the chip's power management against 1.83 for 32x32x16).
+// K advances 64 per step through a two-stage LDS ring that is filled by direct global->LDS
+// loads (no VGPR round trip, no LDS store instructions).
 //
 // LDS tile layout: row r (one W row or one token row) holds its 64 k-values as 8 chunks of
 // 16 bytes, 128 bytes per row, no padding (a direct load writes lane i's 16 bytes at
 // base + 16 i, so padding is not available).  Bank conflicts are avoided by a swizzle that
 // is applied on the GLOBAL side: the lane that fills physical chunk p of row r fetches
 // logical chunk p ^ f(r), f(r) = (r & 7) ^ ((r >> 3) & 1).  Eight consecutive lanes fetch
-// one whole 128-byte row (fully coalesced), and an MFMA operand read (32 rows x one logical
-// chunk) touches every bank group equally.
+// one whole 128-byte row (fully coalesced), and an MFMA operand read (16 rows x four logical
+// chunks) touches every bank group equally.
 //
-// What bounds it (8192 x 28672 x 4096): with random operands the chip is power-managed (1.81 GHz against
-// 2.19 GHz without the ring loads) and every variant with real loads lands at 1.2 PFLOP/s; the vendor library
-// reaches 1.42-1.52 there.  With all-zero operands (full clock) this kernel runs at 1.38, at 1.96 without its
-// loads, 1.70 when every load hits L2 and 1.67 without the ring barrier: the 19 % of the loads that miss L2
-// arrive late and unevenly and the barrier couples all eight waves to the slowest.  Four-wave variants
-// (128 x 128 per wave; also with a four-stage ring of 32-wide K steps and partial vmcnt waits) passed parity
-// and measured 1.08-1.12 on random data.
+// What bounds it (8192 x 28672 x 4096): power.  With all-zero operands (full clock) the kernel runs at
+// 1.69 PFLOP/s: 2.0 without its ring loads, 1.79 when every load hits L2, and the L2 warm-up below closes most
+// of the gap to that (1.47 without it).  With random operands every structural variant lands at 1.20-1.24
+// (1.81 without the ring loads, 1.34 with L2 hits only): the matrix cores, the fragment reads, the L2->LDS
+// stream and the L2 misses each take their share of a fixed power budget, and the clock drops to 1.8 GHz.
+// The vendor library (same 256 x 256 x 64 tile, same MFMA shape) reaches 1.39-1.43 there and 2.14 on zeros.
+// Four-wave variants (128 x 128 per wave; also with a four-stage ring of 32-wide K steps and partial vmcnt
+// waits) passed parity and measured 1.08-1.12 on random data.
 //
 // Epilogue: the residual tile is staged into LDS coalesced, each lane adds its accumulators to
 // its own slots in fp32 and rounds once, and the bf16 tile leaves as full 512-byte row
 // segments.
 #include "common.hpp"
+#include <type_traits>
 
 namespace ts {
 
@@ -43,8 +46,18 @@ typedef __attribute__((address_space(3))) void lds_void;
 // those reads wait for the loads in flight.
 __shared__ uint4 g_stage0[kStageU4];
 __shared__ uint4 g_stage1[kStageU4];
+#ifndef TS_GEMM_PF
+#define TS_GEMM_PF 1
+#endif
 
 __device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0) only
+// Workgroup barrier without the counter waits that __syncthreads() adds (it would wait for every load in
+// flight): the caller has waited for exactly what the ring needs.
+__device__ __forceinline__ void ring_barrier() {
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_barrier();
+  asm volatile("" ::: "memory");
+}
 
 }  // namespace
 
@@ -58,7 +71,6 @@ __device__ __forceinline__ void gemm_mfma256_body(const ts_bf16* __restrict__ A,
                                                   int N, int K, int tiles_m, int tiles_n, ts_bf16* __restrict__ act) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int r32 = lane & 31, g = lane >> 5;
   const int wn = wave & 1, wm = wave >> 1;
 
   // Workgroup -> tile.  Consecutive workgroup ids go round-robin to the 8 XCDs (each with its
@@ -91,6 +103,30 @@ __device__ __forceinline__ void gemm_mfma256_body(const ts_bf16* __restrict__ A,
     woff[q] = (uint32_t)wr * (uint32_t)K * 2u + cl * 16;
     aoff[q] = (uint32_t)min(R, M - 1 - mb) * (uint32_t)K * 2u + cl * 16;
   }
+  // L2 warm-up.  The 32 workgroups an XCD runs at a time form a patch of 8 row tiles x 4 column tiles, so every
+  // operand line is wanted by 8 (W) or 4 (A) workgroups at about the same K step and exactly one of them takes
+  // the L2 miss.  Each workgroup therefore touches, three K steps ahead, its share of the patch's lines: 32 of
+  // its 256 W rows (chosen by its row-tile index in the patch) and 64 of its 256 A rows (by its column-tile
+  // index), 12 lanes per wave, 4 bytes each.  Purely a hint: correctness does not depend on which
+  // workgroups really run together.
+  const char* pfbase;
+  {
+    const int pidx = wave * 12 + min(lane, 11);
+    const int jm = tile_m - first_m, cn = tile_n & 3;
+    if (pidx < 32) {
+      const int R = jm * 32 + pidx;
+      const int wr = GLU ? (R < 128 ? R : F + R - 128) : min(R, N - 1 - nb);
+      pfbase = wtile + (size_t)wr * K * 2;
+    } else {
+      pfbase = atile + (size_t)min(cn * 64 + pidx - 32, M - 1 - mb) * K * 2;
+    }
+  }
+  // The loaded word is only kept alive until the wait that covers it (an ordinary register load, so the
+  // compiler's own counter bookkeeping stays exact); lanes 12..63 repeat lane 11's address.
+  uint32_t warm_prev = 0;
+  auto warm_l2 = [&](int k0) -> uint32_t {
+    return TS_GEMM_PF ? *reinterpret_cast<const uint32_t*>(pfbase + (size_t)k0 * 2) : 0u;
+  };
   // load pair h (0..3) of a K step: one W and one A instruction of this wave
   auto issue_pair = [&](uint4* stage, int k0, int h) {
     uint4* sb = stage + wave * 64 + h * 512;
@@ -98,77 +134,102 @@ __device__ __forceinline__ void gemm_mfma256_body(const ts_bf16* __restrict__ A,
     __builtin_amdgcn_global_load_lds(atile + aoff[h] + (size_t)k0 * 2, (lds_void*)(sb + 2048), 16, 0, 0);
   };
 
-  // ---- operand fragment addresses: row base + swizzled chunk for k-step ks
-  const int f = (r32 & 7) ^ ((r32 >> 3) & 1);
-  int frag_off[4];
+  // ---- operand fragments of the 16x16x32 MFMA: lane (r16, kq) supplies row r16 and the 8 k-values of 16-byte
+  // chunk kq of a 32-wide k-slice, for both operands (which 8 k-values a chunk holds is free as long as both
+  // agree).  16 rows x 128 bytes = 2048 bytes per fragment; the swizzle depends on the row only through r16.
+  const int r16 = lane & 15, kq = lane >> 4;
+  const int f = (r16 & 7) ^ (r16 >> 3);
+  int frag_off[2];
 #pragma unroll
-  for (int ks = 0; ks < 4; ++ks) frag_off[ks] = r32 * 128 + (((ks * 2) ^ g ^ f) * 16);
+  for (int sl = 0; sl < 2; ++sl) frag_off[sl] = r16 * 128 + (((sl * 4 + kq) ^ f) * 16);
   const int wbase = wn * 128 * 128;
   const int abase = 32768 + wm * 64 * 128;
 
-  f32x16 acc[4][2];
+  // acc[i][j]: output columns n = i*16 .. +16 (8 blocks), token rows m = j*16 .. +16 (4 blocks) of the wave tile
+  f32x4 acc[8][4];
 #pragma unroll
-  for (int i = 0; i < 4; ++i)
+  for (int i = 0; i < 8; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j)
+    for (int j = 0; j < 4; ++j)
 #pragma unroll
-      for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.f;
+      for (int e = 0; e < 4; ++e) acc[i][j][e] = 0.f;
 
-  // One K step.  Operand fragments are double buffered in registers: the LDS reads for k-step
-  // ks+1 are issued before the 8 MFMAs of ks and interleaved with them one to one.  The eight
-  // direct loads that fill the other stage are issued first, so that they have the whole step
-  // to land (spreading them over the step measured slower).
-  auto load_frags = [&](const char* st, int ks, U4(&wf)[4], U4(&af)[2]) {
+  // A K step of 64 is four units of 16 MFMAs: (k-slice sl, column half h) = 4 W fragments x the 4 A fragments
+  // of the slice.  Fragments of the next unit are read from LDS while the current unit multiplies.
+  auto load_w = [&](const char* st, int sl, int h, U4(&wf)[4]) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) wf[i].u = *reinterpret_cast<const uint4*>(st + wbase + i * 4096 + frag_off[ks]);
-#pragma unroll
-    for (int j = 0; j < 2; ++j) af[j].u = *reinterpret_cast<const uint4*>(st + abase + j * 4096 + frag_off[ks]);
+    for (int i = 0; i < 4; ++i)
+      wf[i].u = *reinterpret_cast<const uint4*>(st + wbase + (h * 4 + i) * 2048 + frag_off[sl]);
   };
-  auto mfma8 = [&](const U4(&wf)[4], const U4(&af)[2]) {
+  auto load_a = [&](const char* st, int sl, U4(&af)[4]) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) af[j].u = *reinterpret_cast<const uint4*>(st + abase + j * 2048 + frag_off[sl]);
+  };
+  auto mfma16 = [&](auto hc, const U4(&wf)[4], const U4(&af)[4]) {
+    constexpr int h = decltype(hc)::value;
 #pragma unroll
     for (int i = 0; i < 4; ++i)
 #pragma unroll
-      for (int j = 0; j < 2; ++j)
-        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(wf[i].b, af[j].b, acc[i][j], 0, 0, 0);
+      for (int j = 0; j < 4; ++j)
+        acc[h * 4 + i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(wf[i].b, af[j].b, acc[h * 4 + i][j], 0, 0, 0);
   };
-  auto order = [&]() {   // instruction order of the block just written: MFMA, (LDS read, MFMA) x 6, MFMA
+  // instruction order of the unit just written: MFMA, (LDS read, MFMA) x R, the remaining MFMAs
+  auto order = [&](auto rc) {
+    constexpr int R = decltype(rc)::value;
     __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
 #pragma unroll
-    for (int r = 0; r < 6; ++r) {
+    for (int r = 0; r < R; ++r) {
       __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
       __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
     }
-    __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+    __builtin_amdgcn_sched_group_barrier(0x008, 15 - R, 0);
   };
+  using H0 = std::integral_constant<int, 0>;
+  using H1 = std::integral_constant<int, 1>;
+  using R4 = std::integral_constant<int, 4>;
+  using R8 = std::integral_constant<int, 8>;
+  // The last unit of a stage (slice 1, half 1) is read before the barrier that ends the stage and multiplied
+  // after it, next to the first fragment reads of the following stage: the matrix cores have work while
+  // those reads are in flight.  (wB, aB) carry it; zero before the first step.
+  const int nk = K / kBK;
+  const int klast = (nk - 1) * kBK;
+  U4 wA[4], wB[4], aA[4], aB[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i) wB[i].u = aB[i].u = make_uint4(0, 0, 0, 0);
   auto step = [&](const uint4* cur, uint4* nxt, int knext) {
     const char* st = reinterpret_cast<const char*>(cur);
 #pragma unroll
     for (int h = 0; h < 4; ++h) issue_pair(nxt, knext, h);
+    __builtin_amdgcn_sched_barrier(0);
+    const uint32_t warm = warm_l2(min(knext + 2 * kBK, klast));   // issued last: the wait below leaves it in flight
     __builtin_amdgcn_sched_barrier(0);   // keep the loads ahead of the MFMAs they overlap with
-    U4 wf0[4], af0[2], wf1[4], af1[2];
-    load_frags(st, 0, wf0, af0);
+    load_a(st, 0, aA);
+    load_w(st, 0, 0, wA);
+    mfma16(H1{}, wB, aB);                 // slice 1, half 1 of the previous stage
+    order(R8{});
     __builtin_amdgcn_sched_barrier(0);
-    load_frags(st, 1, wf1, af1);
-    mfma8(wf0, af0);
-    order();
+    load_w(st, 0, 1, wB);
+    mfma16(H0{}, wA, aA);
+    order(R4{});
     __builtin_amdgcn_sched_barrier(0);
-    load_frags(st, 2, wf0, af0);
-    mfma8(wf1, af1);
-    order();
+    load_a(st, 1, aB);
+    load_w(st, 1, 0, wA);
+    mfma16(H1{}, wB, aA);
+    order(R8{});
     __builtin_amdgcn_sched_barrier(0);
-    load_frags(st, 3, wf1, af1);
-    mfma8(wf0, af0);
-    order();
+    load_w(st, 1, 1, wB);
+    mfma16(H0{}, wA, aB);
+    order(R4{});
     __builtin_amdgcn_sched_barrier(0);
-    mfma8(wf1, af1);
-    wait_vm0();
-    __syncthreads();
+    // the next stage has landed (all but the newest load, the warm-up) and this one is fully read
+    __builtin_amdgcn_s_waitcnt(TS_GEMM_PF ? 0x0071 : 0x0070);
+    ring_barrier();
+    asm volatile("" ::"v"(warm_prev));   // the previous step's warm-up word has arrived by now
+    warm_prev = warm;
   };
   // Every step prefetches; the last one re-fetches the final K slice into the stage nobody
   // reads any more (cheaper than a second, load-free copy of the step), and its loads have
   // landed before the epilogue reuses the ring.
-  const int nk = K / kBK;
-  const int klast = (nk - 1) * kBK;
 #pragma unroll
   for (int h = 0; h < 4; ++h) issue_pair(g_stage0, 0, h);
   wait_vm0();
@@ -179,6 +240,9 @@ __device__ __forceinline__ void gemm_mfma256_body(const ts_bf16* __restrict__ A,
     step(g_stage1, g_stage0, min((it + 2) * kBK, klast));
   }
   if (it < nk) step(g_stage0, g_stage1, klast);   // odd number of K steps
+  mfma16(H1{}, wB, aB);
+  asm volatile("" ::"v"(warm_prev));   // keeps the last step's warm-up load, which its wait counts on
+  wait_vm0();   // no load may still be in flight towards LDS when the ring is reused and the workgroup ends
 
   // ---- epilogue.  The ring is dead; the two stages now hold the bf16 image of the C tile:
   // rows 0..127 in stage 0, 128..255 in stage 1, 512 bytes per row, unpadded.  Logical 16-byte
@@ -202,30 +266,26 @@ __device__ __forceinline__ void gemm_mfma256_body(const ts_bf16* __restrict__ A,
     }
     __syncthreads();
   }
-  // acc[i][j][e] is D[n = i*32 + (e/4)*8 + g*4 + e%4][m = j*32 + r32] of the wave tile; every
-  // 8-byte slot of the image is read (residual) and written by exactly one lane.
+  // acc[i][j][e] is D[n = i*16 + kq*4 + e][m = j*16 + r16] of the wave tile; every 8-byte slot of the image
+  // is read (residual) and written by exactly one lane.
 #pragma unroll
-  for (int j = 0; j < 2; ++j) {
-    const int m = wm * 64 + j * 32 + r32;
+  for (int j = 0; j < 4; ++j) {
+    const int m = wm * 64 + j * 16 + r16;
     char* row = image_row(m);
-    const int hoff = (g ^ ((m >> 4) & 1)) * 8;
+    const int hoff = ((kq & 1) ^ ((m >> 4) & 1)) * 8;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-#pragma unroll
-      for (int gi = 0; gi < 4; ++gi) {
-        const int ch = wn * 16 + i * 4 + gi;
-        uint2* slot = reinterpret_cast<uint2*>(row + ((ch ^ (m & 15)) * 16) + hoff);
-        float v0 = acc[i][j][gi * 4 + 0], v1 = acc[i][j][gi * 4 + 1], v2 = acc[i][j][gi * 4 + 2],
-              v3 = acc[i][j][gi * 4 + 3];
-        if (residual != nullptr) {
-          const uint2 r = *slot;
-          v0 += bf_lo(r.x); v1 += bf_hi(r.x); v2 += bf_lo(r.y); v3 += bf_hi(r.y);
-        }
-        uint2 o;
-        o.x = pack_bf16(v0, v1);
-        o.y = pack_bf16(v2, v3);
-        *slot = o;
+    for (int i = 0; i < 8; ++i) {
+      const int ch = wn * 16 + i * 2 + (kq >> 1);
+      uint2* slot = reinterpret_cast<uint2*>(row + ((ch ^ (m & 15)) * 16) + hoff);
+      float v0 = acc[i][j][0], v1 = acc[i][j][1], v2 = acc[i][j][2], v3 = acc[i][j][3];
+      if (residual != nullptr) {
+        const uint2 r = *slot;
+        v0 += bf_lo(r.x); v1 += bf_hi(r.x); v2 += bf_lo(r.y); v3 += bf_hi(r.y);
       }
+      uint2 o;
+      o.x = pack_bf16(v0, v1);
+      o.y = pack_bf16(v2, v3);
+      *slot = o;
     }
   }
   __syncthreads();
