@@ -96,13 +96,13 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(const ts_bf16* _
     for (int kt = 0; kt < 2; ++kt) {
       const int key = min(k0 + kt * 16 + l16, end - 1);
 #pragma unroll
-      for (int j = 0; j < KSTEPS; ++j) kf[kt][j].u = ldg16(kbase + (size_t)key * D + (j * 4 + gq) * 8);
+      for (int j = 0; j < KSTEPS; ++j) kf[kt][j].u = ldg16_stream(kbase + (size_t)key * D + (j * 4 + gq) * 8);
     }
 #pragma unroll
     for (int i = 0; i < VLOADS; ++i) {
       const int c = lane + 64 * i;
       const int key = min(k0 + c / CPR, end - 1);
-      vf[i].u = ldg16(vbase + (size_t)key * D + (c % CPR) * 8);
+      vf[i].u = ldg16_stream(vbase + (size_t)key * D + (c % CPR) * 8);
     }
   };
 

