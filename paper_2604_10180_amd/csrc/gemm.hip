@@ -45,9 +45,12 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(SkinnyArgs a) {
   constexpr int LDS_ROW = 17;  // uint4 per staged row: 16 data + 1 pad (272 B stride, conflict-free b128 reads)
   extern __shared__ uint4 smem[];
   uint4(*lds)[ROWS][LDS_ROW] = reinterpret_cast<uint4(*)[ROWS][LDS_ROW]>(smem);
+  // behind the activation ring, per wave, a W stage: 16 rows x 16 chunks, chunk c of row r at chunk c ^ r
+  // (conflict-free whole-row writes and operand reads), reused for every row block and slab
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
+  uint4* wst = smem + NS * ROWS * LDS_ROW + wave * 256;
   int row0 = 0, Mtot = a.M;
   const ts_bf16* W = a.W;
   if (GROUPED) {
@@ -62,11 +65,29 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(SkinnyArgs a) {
   const int kbeg = blockIdx.y * a.kslice;
   const int kend = min(K, kbeg + a.kslice);
 
-  const ts_bf16* wrow[NT];
+  // W is fetched as whole 256-byte row slabs (load i of a 16-row block: lane (l16, g) takes chunk l16 of row
+  // 4i + g, so an instruction covers 1 KiB of whole cache lines): only in that form does the non-temporal hint
+  // pay (7.0 against 6.3 TB/s for a pure read stream; with 16 rows x 64 bytes per instruction, which is what
+  // reading MFMA operands straight from global amounts to, it costs 3 %).  The wave's LDS stage turns the slab
+  // into operand fragments.
+  // Used up to 32 token rows (70B shapes: gate/up 193 -> 147 us, 6.4 TB/s).  At 64 rows it measured the same
+  // for the dense projections and 10 % worse for the grouped one, whose workgroups then fit two instead of
+  // three to a CU; those keep reading operands straight from global: fragment j of lane (l16, g) is chunk
+  // j*4 + g of row l16, 64 contiguous bytes per row and instruction.
+  constexpr bool WSTAGE = MT <= 2;
+  const ts_bf16* wrow[NT][WSTAGE ? 4 : 1];
 #pragma unroll
   for (int nt = 0; nt < NT; ++nt) {
-    int n = min(nbase + nt * 16 + l16, N - 1);
-    wrow[nt] = W + (size_t)n * K;
+    if constexpr (WSTAGE) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        int n = min(nbase + nt * 16 + 4 * i + g, N - 1);
+        wrow[nt][i] = W + (size_t)n * K + l16 * 8;
+      }
+    } else {
+      int n = min(nbase + nt * 16 + l16, N - 1);
+      wrow[nt][0] = W + (size_t)n * K + g * 8;
+    }
   }
   const int st_r = tid >> 4, st_c = tid & 15;  // staging: row st_r + 16*i, chunk st_c
 
@@ -100,16 +121,18 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(SkinnyArgs a) {
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
-        for (int j = 0; j < 4; ++j) dst[nt][j].u = ldg16(wrow[nt] + k0 + (j * 4 + g) * 8);
+        for (int j = 0; j < 4; ++j)
+          dst[nt][j].u = WSTAGE ? ldg16_stream(wrow[nt][WSTAGE ? j : 0] + k0) : ldg16(wrow[nt][0] + k0 + j * 32);
     };
     auto load_w_tail = [&](int k0, U4(&dst)[NT][4]) {
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          const int k = k0 + (j * 4 + g) * 8;
-          const bool ok = k < kend;
-          dst[nt][j].u = ldg16_or_zero(wrow[nt] + (ok ? k : kbeg), ok);
+          const int lo = (WSTAGE ? l16 : g) * 8;          // lane offset held in the pointer
+          const int k = WSTAGE ? k0 : k0 + j * 32;
+          const bool ok = k + lo < kend;
+          dst[nt][j].u = ldg16_or_zero(wrow[nt][WSTAGE ? j : 0] + (ok ? k : kbeg - lo), ok);
         }
     };
     auto load_a = [&](int k0) {
@@ -123,7 +146,25 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(SkinnyArgs a) {
 #pragma unroll
       for (int i = 0; i < MT; ++i) lds[buf][st_r + 16 * i][st_c] = areg[i].u;
     };
-    auto compute = [&](int buf, U4(&w)[NT][4]) {
+    auto compute = [&](int buf, U4(&wraw)[NT][4]) {
+      // slab rows -> operand fragments through the wave's stage: fragment j of lane (l16, g) is chunk
+      // j*4 + g of row l16.  A wave's LDS operations execute in order, so the next block's writes cannot
+      // overtake these reads.
+      U4 w[NT][4];
+#pragma unroll
+      for (int nt = 0; nt < NT; ++nt) {
+        if constexpr (WSTAGE) {
+#pragma unroll
+          for (int i = 0; i < 4; ++i) wst[(4 * i + g) * 16 + (l16 ^ (4 * i + g))] = wraw[nt][i].u;
+          __builtin_amdgcn_wave_barrier();
+#pragma unroll
+          for (int j = 0; j < 4; ++j) w[nt][j].u = wst[l16 * 16 + ((j * 4 + g) ^ l16)];
+          __builtin_amdgcn_wave_barrier();
+        } else {
+#pragma unroll
+          for (int j = 0; j < 4; ++j) w[nt][j] = wraw[nt][j];
+        }
+      }
       // read a whole k-step of activation fragments before the MFMAs that use them, so the
       // LDS latency is paid once per step instead of once per MFMA
 #pragma unroll
@@ -518,7 +559,7 @@ void launch_skinny_mt(const SkinnyArgs& a, int NT, dim3 grid, hipStream_t s, int
       auto go = [&](auto nt_c, auto w_c) {
         constexpr int NTc = decltype(nt_c)::value, Wc = decltype(w_c)::value;
         constexpr int NS = skinny_stages<MT, NTc>();
-        const size_t smem = (size_t)NS * MT * 16 * 17 * sizeof(uint4);
+        const size_t smem = ((size_t)NS * MT * 16 * 17 + (MT <= 2 ? Wc * 256 : 0)) * sizeof(uint4);
         allow_lds(gemm_skinny_kernel<MT, NTc, GROUPED, NS, Wc>, smem);
         TS_LAUNCH("gemm_skinny", (gemm_skinny_kernel<MT, NTc, GROUPED, NS, Wc>), grid, dim3(64 * Wc), smem, s, a);
       };
@@ -533,12 +574,12 @@ void launch_skinny_mt(const SkinnyArgs& a, int NT, dim3 grid, hipStream_t s, int
   }
   if (NT == 2) {
     constexpr int NS = skinny_stages<MT, 2>();
-    const size_t smem = (size_t)NS * MT * 16 * 17 * sizeof(uint4);
+    const size_t smem = ((size_t)NS * MT * 16 * 17 + (MT <= 2 ? 4 * 256 : 0)) * sizeof(uint4);
     allow_lds(gemm_skinny_kernel<MT, 2, GROUPED, NS>, smem);
     TS_LAUNCH("gemm_skinny", (gemm_skinny_kernel<MT, 2, GROUPED, NS>), grid, dim3(256), smem, s, a);
   } else {
     constexpr int NS = skinny_stages<MT, 1>();
-    const size_t smem = (size_t)NS * MT * 16 * 17 * sizeof(uint4);
+    const size_t smem = ((size_t)NS * MT * 16 * 17 + (MT <= 2 ? 4 * 256 : 0)) * sizeof(uint4);
     allow_lds(gemm_skinny_kernel<MT, 1, GROUPED, NS>, smem);
     TS_LAUNCH("gemm_skinny", (gemm_skinny_kernel<MT, 1, GROUPED, NS>), grid, dim3(256), smem, s, a);
   }
