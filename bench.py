@@ -174,15 +174,17 @@ def time_pipeline(B, torch, wl, desc, dev_set, io_cpu, dev, steps, warmup, extra
     stride = B.ts_pipeline_slot_stride(desc, per, per, full)
     staging = torch.zeros(max(stride * n_mb, 16), dtype=torch.uint8, device=dev)
     host = torch.zeros(max(stride * n_mb, 16), dtype=torch.uint8).pin_memory()
-    half = (B.ts_layer_workspace_bytes(desc, per, per) + 255) // 256 * 256
-    ws = torch.zeros(2 * half, dtype=torch.uint8, device=dev)
+    slot = (B.ts_layer_workspace_bytes(desc, per, per) + 255) // 256 * 256
+    ws = torch.zeros(n_mb * slot, dtype=torch.uint8, device=dev)   # a workspace slot per micro-batch
     pipe = B.ts_pipeline_create(desc, n_mb)
     streams = [torch.cuda.Stream(), torch.cuda.Stream()]
     copy = torch.cuda.Stream()
-    out = {"micro_batches": n_mb, "sequences_per_micro_batch": per, "boundary_bytes_per_step": int(stride * n_mb)}
+    out = {"micro_batches": n_mb, "sequences_per_micro_batch": per, "workspace_slots": n_mb,
+           "boundary_bytes_per_step": int(stride * n_mb)}
     try:
         cases = [("no_copies", 0, B.TS_PIPE_COPY_SIDE_STREAM), ("side_stream", full, B.TS_PIPE_COPY_SIDE_STREAM),
-                 ("coalesced", full, B.TS_PIPE_COPY_COALESCED), ("serialised", full, B.TS_PIPE_COPY_SERIALISED)]
+                 ("coalesced", full, B.TS_PIPE_COPY_COALESCED), ("coalesced_halves", full, B.TS_PIPE_COPY_COALESCED_HALVES),
+                 ("serialised", full, B.TS_PIPE_COPY_SERIALISED)]
         # only the cut edges of a planned placement (the slot layout is sized for the full mask, so any subset fits)
         for label, m in (extra_masks or {}).items():
             cases.append((f"planned_{label}", m & full, B.TS_PIPE_COPY_SIDE_STREAM))
@@ -195,8 +197,11 @@ def time_pipeline(B, torch, wl, desc, dev_set, io_cpu, dev, steps, warmup, extra
             t0 = time.perf_counter()
             for _ in range(steps):
                 one()
+            t1 = time.perf_counter()
             torch.cuda.synchronize()
             out[name + "_ms"] = round((time.perf_counter() - t0) * 1e3 / steps, 4)
+            # host time to enqueue a step: if it is close to the step time the host, not the GPU, sets the pace
+            out.setdefault("host_enqueue_ms", {})[name] = round((t1 - t0) * 1e3 / steps, 4)
     finally:
         B.ts_pipeline_destroy(pipe)
     # background replication of the KV delta on a fourth stream, on top of the coalesced sends
@@ -224,6 +229,7 @@ def time_pipeline(B, torch, wl, desc, dev_set, io_cpu, dev, steps, warmup, extra
     out["tokens_per_s_side_stream"] = round(wl.B / (out["side_stream_ms"] * 1e-3), 1)
     out["overlap_ratio"] = round(out["side_stream_ms"] / out["no_copies_ms"], 4)
     out["overlap_ratio_coalesced"] = round(out["coalesced_ms"] / out["no_copies_ms"], 4)
+    out["overlap_ratio_coalesced_halves"] = round(out["coalesced_halves_ms"] / out["no_copies_ms"], 4)
     return out
 
 

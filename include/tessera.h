@@ -277,7 +277,10 @@ int ts_layer_forward(const ts_layer_desc* desc, const ts_layer_weights* w, const
  * memory of the same size that the device can address (hipHostMalloc, or a
  * torch tensor created with pin_memory): the pack kernel stores to it
  * directly, no copy-engine command is issued.  ws: device, >= 2 * ts_layer_workspace_bytes(Tmax,Bmax)
- * rounded up to 256 each, where Tmax/Bmax are the largest over micro-batches.
+ * rounded up to 256 each, where Tmax/Bmax are the largest over micro-batches.  The step uses as many
+ * workspace slots of that size as ws_bytes holds (at most n_mb): micro-batch i works in slot i % nslot and
+ * waits, before it starts, for the transfers of the micro-batch that used the slot before it.  With n_mb
+ * slots no micro-batch waits for a transfer of its own step.
  * All micro-batches must flag the same boundaries; their T may differ (the
  * layout is computed for each T; slot_stride uses the largest).
  * copy_mode: TS_PIPE_COPY_SIDE_STREAM sends every flagged boundary as soon as its kernel is enqueued (one
@@ -286,6 +289,10 @@ int ts_layer_forward(const ts_layer_desc* desc, const ts_layer_weights* w, const
  * points of the layer (after RoPE, after the second norm, after SwiGLU, at the end), each send carrying
  * the flagged boundaries produced since the previous one: half the events between the compute kernels
  * (an event costs the compute stream about 2 us), same bytes in the same slots.
+ * TS_PIPE_COPY_COALESCED_HALVES sends twice per layer (after the attention half, i.e. once x2 exists, and
+ * at the end; a send carries at most four tensors, so a layer with more than eight boundaries sends a third
+ * time): a quarter of the events.  A boundary then leaves up to half a layer after it was produced, which
+ * costs a consumer on another GPU latency, not throughput.
  * The call returns after enqueueing; steps may be enqueued back to back (each waits for the transfers of
  * the previous one that still read its workspace half); the caller synchronises the streams before it
  * reads the slots or frees the buffers.
@@ -293,6 +300,7 @@ int ts_layer_forward(const ts_layer_desc* desc, const ts_layer_weights* w, const
 #define TS_PIPE_COPY_SIDE_STREAM 0
 #define TS_PIPE_COPY_SERIALISED 1
 #define TS_PIPE_COPY_COALESCED 2
+#define TS_PIPE_COPY_COALESCED_HALVES 3
 typedef struct ts_pipeline ts_pipeline;
 int ts_pipeline_create(const ts_layer_desc* desc, int max_micro_batches, ts_pipeline** out);
 void ts_pipeline_destroy(ts_pipeline* p);

@@ -74,7 +74,7 @@ class PlanProblem(C.Structure):
 
 
 TS_PLAN_THROUGHPUT, TS_PLAN_LATENCY = 0, 1
-TS_PIPE_COPY_SIDE_STREAM, TS_PIPE_COPY_SERIALISED, TS_PIPE_COPY_COALESCED = 0, 1, 2
+TS_PIPE_COPY_SIDE_STREAM, TS_PIPE_COPY_SERIALISED, TS_PIPE_COPY_COALESCED, TS_PIPE_COPY_COALESCED_HALVES = 0, 1, 2, 3
 
 
 def _load() -> C.CDLL:

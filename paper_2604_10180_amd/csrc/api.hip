@@ -6,6 +6,7 @@
 #include <cmath>
 #include <new>
 #include <vector>
+#include <algorithm>
 
 #include "common.hpp"
 
@@ -492,9 +493,11 @@ struct ts_pipeline {
   char* delta_host = nullptr;
   size_t delta_bytes = 0;
   bool delta_on = false;
-  // what the previous step left in flight on the side streams, per workspace half (-1: nothing)
-  int prev_packed[2] = {-1, -1};
-  int prev_kv_sent[2] = {-1, -1};
+  // what the previous step left in flight on the side streams, per workspace slot (-1: nothing), and the slot
+  // geometry it used (a step with another geometry waits for all of it)
+  std::vector<int> prev_packed, prev_kv_sent;   // [max_mb]
+  size_t prev_slot_bytes = 0;
+  int prev_nslot = 0;
 };
 
 int ts_pipeline_create(const ts_layer_desc* desc, int max_micro_batches, ts_pipeline** out) {
@@ -506,6 +509,8 @@ int ts_pipeline_create(const ts_layer_desc* desc, int max_micro_batches, ts_pipe
   TS_REQUIRE(p != nullptr, TS_ERR_INVALID_ARG, "ts_pipeline_create: out of host memory");
   p->desc = *desc;
   p->max_mb = max_micro_batches;
+  p->prev_packed.assign(max_micro_batches, -1);
+  p->prev_kv_sent.assign(max_micro_batches, -1);
   const int nbe = max_micro_batches * TS_NB_MOE;
   const int n = nbe + 3 * max_micro_batches;
   for (int i = 0; i < n; ++i) {
@@ -586,7 +591,7 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
   TS_REQUIRE(p != nullptr && w != nullptr && mb != nullptr && compute_streams != nullptr, TS_ERR_INVALID_ARG,
              "ts_pipeline_step: null argument");
   TS_REQUIRE(n_mb >= 1 && n_mb <= p->max_mb, TS_ERR_INVALID_ARG, "ts_pipeline_step: n_mb=%d outside [1,%d]", n_mb, p->max_mb);
-  TS_REQUIRE(copy_mode >= TS_PIPE_COPY_SIDE_STREAM && copy_mode <= TS_PIPE_COPY_COALESCED,
+  TS_REQUIRE(copy_mode >= TS_PIPE_COPY_SIDE_STREAM && copy_mode <= TS_PIPE_COPY_COALESCED_HALVES,
              TS_ERR_INVALID_ARG, "ts_pipeline_step: unknown copy mode %d", copy_mode);
   const ts_layer_desc& d = p->desc;
   const int nb = d.E > 0 ? TS_NB_MOE : TS_NB_DENSE;
@@ -612,17 +617,26 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
   TS_REQUIRE(!p->delta_on || p->delta_bytes >= dstride * (size_t)n_mb, TS_ERR_WORKSPACE,
              "ts_pipeline_step: KV delta slots %zu bytes < required %zu", p->delta_bytes, dstride * (size_t)n_mb);
 
+  // Micro-batch i works in workspace slot i % nslot, with as many slots as the workspace holds (two at least):
+  // with a slot of its own a micro-batch never waits for the transfers of an earlier one of the same step
+  // (with two slots every micro-batch from the third on starts only after the last send of the one two before
+  // it, which cannot begin before that one's last kernel).
+  const int nslot = (int)std::min<size_t>((size_t)n_mb, std::max<size_t>(2, ws_bytes / half));
+  const bool same_geometry = p->prev_nslot == nslot && p->prev_slot_bytes == half;
   for (int i = 0; i < n_mb; ++i) {
     hipStream_t s = cs[i & 1];
-    char* wsh = reinterpret_cast<char*>(ws) + (size_t)(i & 1) * half;
-    // the workspace half is reused by every second micro-batch: wait until its boundary
-    // tensors have been packed before overwriting them
-    if (i >= 2 && boundary_mask != 0 && copy_mode != TS_PIPE_COPY_SERIALISED)
-      TS_HIP(hipStreamWaitEvent(s, p->packed_ev[i - 2], 0));
-    if (i >= 2 && p->delta_on) TS_HIP(hipStreamWaitEvent(s, p->kv_sent_ev[i - 2], 0));   // its rows sit in that half
-    if (i < 2) {   // steps may follow each other without a host synchronisation: the previous step's last users
-      if (p->prev_packed[i] >= 0) TS_HIP(hipStreamWaitEvent(s, p->packed_ev[p->prev_packed[i]], 0));
-      if (p->prev_kv_sent[i] >= 0) TS_HIP(hipStreamWaitEvent(s, p->kv_sent_ev[p->prev_kv_sent[i]], 0));
+    char* wsh = reinterpret_cast<char*>(ws) + (size_t)(i % nslot) * half;
+    // a slot is reused by every nslot-th micro-batch: wait until its boundary tensors have been packed before
+    // overwriting them
+    if (i >= nslot && boundary_mask != 0 && copy_mode != TS_PIPE_COPY_SERIALISED)
+      TS_HIP(hipStreamWaitEvent(s, p->packed_ev[i - nslot], 0));
+    if (i >= nslot && p->delta_on) TS_HIP(hipStreamWaitEvent(s, p->kv_sent_ev[i - nslot], 0));   // its rows sit in that slot
+    if (i < nslot) {   // steps may follow each other without a host synchronisation: the previous step's last users
+      for (int h = 0; h < p->prev_nslot; ++h) {
+        if (same_geometry && h != i) continue;   // same slots as last time: only this slot's last user matters
+        if (p->prev_packed[h] >= 0) TS_HIP(hipStreamWaitEvent(s, p->packed_ev[p->prev_packed[h]], 0));
+        if (p->prev_kv_sent[h] >= 0) TS_HIP(hipStreamWaitEvent(s, p->kv_sent_ev[p->prev_kv_sent[h]], 0));
+      }
     }
     const LayerPlan plan = plan_layer(d, mb[i].T, mb[i].B);
     size_t offs[TS_NB_MOE + 1];
@@ -633,7 +647,8 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
     char* slot_host = reinterpret_cast<char*>(pinned_host) + (size_t)i * stride;
     int ordinal = 0;
     CopySegments pending{};
-    const bool coalesce = copy_mode == TS_PIPE_COPY_COALESCED;
+    const bool halves = copy_mode == TS_PIPE_COPY_COALESCED_HALVES;
+    const bool coalesce = copy_mode == TS_PIPE_COPY_COALESCED || halves;
     const bool serial = copy_mode == TS_PIPE_COPY_SERIALISED;
     // send what is pending: one event on the compute stream, one pack launch on the copy stream
     auto flush = [&](int index) -> int {
@@ -681,19 +696,23 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
       }
       // coalesced sends leave after RoPE, after the second norm, after SwiGLU and at the end of the layer (the
       // last one is then only the layer output: the next user of this workspace half waits for it)
-      if (coalesce && (index == TS_B_QKV || index == TS_B_H2 || index == TS_B_ACT || index == nb - 1 || pending.n == 4))
-        return flush(index);
+      // (TS_PIPE_COPY_COALESCED_HALVES: after the attention half of the layer and at the end)
+      const bool at_point = halves ? index == TS_B_X2 : (index == TS_B_QKV || index == TS_B_H2 || index == TS_B_ACT);
+      if (coalesce && (at_point || index == nb - 1 || pending.n == 4)) return flush(index);
       return TS_OK;
     };
     rc = layer_forward_impl(d, *w, mb[i], wsh, s, hook);
     if (rc != TS_OK) return rc;
     if (boundary_mask != 0 && copy_mode != TS_PIPE_COPY_SERIALISED) TS_HIP(hipEventRecord(p->packed_ev[i], copy));
   }
-  for (int h = 0; h < 2; ++h) {
-    const int last = n_mb - 1 - (((n_mb - 1) & 1) != h ? 1 : 0);   // last micro-batch that used half h
+  for (int h = 0; h < nslot; ++h) {
+    int last = -1;   // last micro-batch that used slot h
+    for (int i = h; i < n_mb; i += nslot) last = i;
     p->prev_packed[h] = (last >= 0 && boundary_mask != 0 && copy_mode != TS_PIPE_COPY_SERIALISED) ? last : -1;
     p->prev_kv_sent[h] = (last >= 0 && p->delta_on) ? last : -1;
   }
+  p->prev_nslot = nslot;
+  p->prev_slot_bytes = half;
   return TS_OK;
 }
 

@@ -208,11 +208,11 @@ __global__ __launch_bounds__(256) void copy16_kernel(const uint4* __restrict__ s
 // Several boundary tensors in one launch (segments are consecutive in both destination slots).
 __global__ __launch_bounds__(256) void copy16_multi_kernel(CopySegments segs, uint4* __restrict__ dst,
                                                            uint4* __restrict__ dst2) {
-  const size_t stride = (size_t)gridDim.x * 256;
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
   for (int g = 0; g < segs.n; ++g) {
     const uint4* src = reinterpret_cast<const uint4*>(segs.src[g]);
     const size_t base = segs.dst_off16[g], n16 = segs.n16[g];
-    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n16; i += stride) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) {
       const uint4 v = src[i];
       dst[base + i] = v;
       dst2[base + i] = v;
@@ -222,7 +222,11 @@ __global__ __launch_bounds__(256) void copy16_multi_kernel(CopySegments segs, ui
 
 int launch_copy16_multi(const CopySegments& segs, void* dst, void* dst2, hipStream_t s) {
   if (segs.n == 0) return TS_OK;
-  TS_LAUNCH("copy16", copy16_multi_kernel, dim3(32), dim3(256), 0, s, segs, reinterpret_cast<uint4*>(dst),
+  // Four workgroups: the bandwidth-bound compute kernels beside it run one or two workgroups per CU and end
+  // when their slowest CU ends, so every CU the pack kernel's PCIe stores sit on costs them time (measured on
+  // the 70B pipelined step: 2 or 4 workgroups +4.5 % over the copy-free step, 32: +6.5 %, 512 single-wave
+  // ones: +8.5 %; one workgroup cannot keep up with the step).
+  TS_LAUNCH("copy16", copy16_multi_kernel, dim3(4), dim3(256), 0, s, segs, reinterpret_cast<uint4*>(dst),
             reinterpret_cast<uint4*>(dst2));
   TS_LAUNCH_CHECK("copy16");
   return TS_OK;
@@ -259,7 +263,7 @@ int launch_copy16(const void* src, void* dst, size_t bytes, hipStream_t s, void*
   size_t n16 = bytes / 16;
   unsigned blocks = (unsigned)((n16 + 255) / 256);
   // few workgroups when the copy leaves over PCIe: it must not take CUs from the compute streams
-  const unsigned cap = dst2 != nullptr ? 32 : 2048;
+  const unsigned cap = dst2 != nullptr ? 4 : 2048;
   if (blocks > cap) blocks = cap;
   TS_LAUNCH("copy16", copy16_kernel, dim3(blocks), dim3(256), 0, s, reinterpret_cast<const uint4*>(src),
             reinterpret_cast<uint4*>(dst), reinterpret_cast<uint4*>(dst2), n16);

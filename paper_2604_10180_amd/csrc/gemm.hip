@@ -42,15 +42,18 @@ template <int MT, int NT, bool GROUPED, int NS, int WAVES = 4>
 __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(SkinnyArgs a) {
   constexpr int ROWS = MT * 16;
   constexpr int D = NS - 1;    // prefetch distance in 128-wide K slabs
+  // activation slabs in LDS: the D the ring needs where the W stage shares the LDS, else one per register stage
+  // (stage indices are then compile-time constants)
+  constexpr int AST = (MT <= 2) ? D : NS;
   constexpr int LDS_ROW = 17;  // uint4 per staged row: 16 data + 1 pad (272 B stride, conflict-free b128 reads)
   extern __shared__ uint4 smem[];
   uint4(*lds)[ROWS][LDS_ROW] = reinterpret_cast<uint4(*)[ROWS][LDS_ROW]>(smem);
-  // behind the activation ring, per wave, a W stage: 16 rows x 16 chunks, chunk c of row r at chunk c ^ r
-  // (conflict-free whole-row writes and operand reads), reused for every row block and slab
+  // behind the activation ring, per wave, a W stage of 16 rows x 8 chunks (half a slab), chunk c of row r at
+  // chunk c ^ (r & 7) ^ (r >> 3) (conflict-free whole-line writes and operand reads), reused for every half
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int l16 = lane & 15, g = lane >> 4;
-  uint4* wst = smem + NS * ROWS * LDS_ROW + wave * 256;
+  uint4* wst = smem + AST * ROWS * LDS_ROW + wave * 128;
   int row0 = 0, Mtot = a.M;
   const ts_bf16* W = a.W;
   if (GROUPED) {
@@ -65,15 +68,11 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(SkinnyArgs a) {
   const int kbeg = blockIdx.y * a.kslice;
   const int kend = min(K, kbeg + a.kslice);
 
-  // W is fetched as whole 256-byte row slabs (load i of a 16-row block: lane (l16, g) takes chunk l16 of row
-  // 4i + g, so an instruction covers 1 KiB of whole cache lines): only in that form does the non-temporal hint
-  // pay (7.0 against 6.3 TB/s for a pure read stream; with 16 rows x 64 bytes per instruction, which is what
-  // reading MFMA operands straight from global amounts to, it costs 3 %).  The wave's LDS stage turns the slab
-  // into operand fragments.
-  // Used up to 32 token rows (70B shapes: gate/up 193 -> 147 us, 6.4 TB/s).  At 64 rows it measured the same
-  // for the dense projections and 10 % worse for the grouped one, whose workgroups then fit two instead of
-  // three to a CU; those keep reading operands straight from global: fragment j of lane (l16, g) is chunk
-  // j*4 + g of row l16, 64 contiguous bytes per row and instruction.
+  // W is fetched as whole cache lines (load i of a 16-row block: lane takes chunk lane % 8 of line i / 2 of
+  // row 8 (i % 2) + lane / 8, so an instruction covers eight whole 128-byte lines): only in that form does
+  // the non-temporal hint pay (7.0 against 6.3 TB/s for a pure read stream; with 16 rows x 64 bytes per
+  // instruction, which is what reading MFMA operands straight from global amounts to, it costs 3 %).  The
+  // wave's LDS stage turns each half slab into operand fragments.
   constexpr bool WSTAGE = MT <= 2;
   const ts_bf16* wrow[NT][WSTAGE ? 4 : 1];
 #pragma unroll
@@ -81,8 +80,8 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(SkinnyArgs a) {
     if constexpr (WSTAGE) {
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        int n = min(nbase + nt * 16 + 4 * i + g, N - 1);
-        wrow[nt][i] = W + (size_t)n * K + l16 * 8;
+        int n = min(nbase + nt * 16 + 8 * (i & 1) + (lane >> 3), N - 1);
+        wrow[nt][i] = W + (size_t)n * K + (8 * (i >> 1) + (lane & 7)) * 8;
       }
     } else {
       int n = min(nbase + nt * 16 + l16, N - 1);
@@ -129,7 +128,7 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(SkinnyArgs a) {
       for (int nt = 0; nt < NT; ++nt)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          const int lo = (WSTAGE ? l16 : g) * 8;          // lane offset held in the pointer
+          const int lo = (WSTAGE ? 8 * (j >> 1) + (lane & 7) : g) * 8;   // lane offset held in the pointer
           const int k = WSTAGE ? k0 : k0 + j * 32;
           const bool ok = k + lo < kend;
           dst[nt][j].u = ldg16_or_zero(wrow[nt][WSTAGE ? j : 0] + (ok ? k : kbeg - lo), ok);
@@ -147,19 +146,26 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(SkinnyArgs a) {
       for (int i = 0; i < MT; ++i) lds[buf][st_r + 16 * i][st_c] = areg[i].u;
     };
     auto compute = [&](int buf, U4(&wraw)[NT][4]) {
-      // slab rows -> operand fragments through the wave's stage: fragment j of lane (l16, g) is chunk
-      // j*4 + g of row l16.  A wave's LDS operations execute in order, so the next block's writes cannot
-      // overtake these reads.
+      // slab lines -> operand fragments through the wave's stage, half a slab at a time: fragment j of lane
+      // (l16, g) is chunk j*4 + g of row l16.  A wave's LDS operations execute in order, so the next half's
+      // writes cannot overtake these reads.
       U4 w[NT][4];
 #pragma unroll
       for (int nt = 0; nt < NT; ++nt) {
         if constexpr (WSTAGE) {
 #pragma unroll
-          for (int i = 0; i < 4; ++i) wst[(4 * i + g) * 16 + (l16 ^ (4 * i + g))] = wraw[nt][i].u;
-          __builtin_amdgcn_wave_barrier();
+          for (int h = 0; h < 2; ++h) {
 #pragma unroll
-          for (int j = 0; j < 4; ++j) w[nt][j].u = wst[l16 * 16 + ((j * 4 + g) ^ l16)];
-          __builtin_amdgcn_wave_barrier();
+            for (int ii = 0; ii < 2; ++ii) {
+              const int r = 8 * ii + (lane >> 3);
+              wst[r * 8 + ((lane & 7) ^ (r & 7) ^ (r >> 3))] = wraw[nt][2 * h + ii].u;
+            }
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int jj = 0; jj < 2; ++jj)
+              w[nt][2 * h + jj].u = wst[l16 * 8 + ((jj * 4 + g) ^ (l16 & 7) ^ (l16 >> 3))];
+            __builtin_amdgcn_wave_barrier();
+          }
         } else {
 #pragma unroll
           for (int j = 0; j < 4; ++j) w[nt][j] = wraw[nt][j];
@@ -191,13 +197,13 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(SkinnyArgs a) {
       auto step = [&](auto checked, auto stage, int it) {
         constexpr bool CHECKED = decltype(checked)::value;
         constexpr int u = decltype(stage)::value;
-        if (!CHECKED || it + D - 1 < nfull) store_a((u + D - 1) % NS);
+        if (!CHECKED || it + D - 1 < nfull) store_a(WSTAGE ? (it + D - 1) % AST : (u + D - 1) % NS);
         if (!CHECKED || it + D < nfull) {
           const int kn = slab(it + D);
           load_a(kn);
           load_w(kn, wbuf[(u + D) % NS]);
         }
-        compute(u, wbuf[u]);
+        compute(WSTAGE ? it % AST : u, wbuf[u]);
         __syncthreads();
       };
       using T_ = std::true_type;
@@ -559,7 +565,7 @@ void launch_skinny_mt(const SkinnyArgs& a, int NT, dim3 grid, hipStream_t s, int
       auto go = [&](auto nt_c, auto w_c) {
         constexpr int NTc = decltype(nt_c)::value, Wc = decltype(w_c)::value;
         constexpr int NS = skinny_stages<MT, NTc>();
-        const size_t smem = ((size_t)NS * MT * 16 * 17 + (MT <= 2 ? Wc * 256 : 0)) * sizeof(uint4);
+        const size_t smem = ((size_t)(MT <= 2 ? NS - 1 : NS) * MT * 16 * 17 + (MT <= 2 ? Wc * 128 : 0)) * sizeof(uint4);
         allow_lds(gemm_skinny_kernel<MT, NTc, GROUPED, NS, Wc>, smem);
         TS_LAUNCH("gemm_skinny", (gemm_skinny_kernel<MT, NTc, GROUPED, NS, Wc>), grid, dim3(64 * Wc), smem, s, a);
       };
@@ -574,12 +580,12 @@ void launch_skinny_mt(const SkinnyArgs& a, int NT, dim3 grid, hipStream_t s, int
   }
   if (NT == 2) {
     constexpr int NS = skinny_stages<MT, 2>();
-    const size_t smem = ((size_t)NS * MT * 16 * 17 + (MT <= 2 ? 4 * 256 : 0)) * sizeof(uint4);
+    const size_t smem = ((size_t)(MT <= 2 ? NS - 1 : NS) * MT * 16 * 17 + (MT <= 2 ? 4 * 128 : 0)) * sizeof(uint4);
     allow_lds(gemm_skinny_kernel<MT, 2, GROUPED, NS>, smem);
     TS_LAUNCH("gemm_skinny", (gemm_skinny_kernel<MT, 2, GROUPED, NS>), grid, dim3(256), smem, s, a);
   } else {
     constexpr int NS = skinny_stages<MT, 1>();
-    const size_t smem = ((size_t)NS * MT * 16 * 17 + (MT <= 2 ? 4 * 256 : 0)) * sizeof(uint4);
+    const size_t smem = ((size_t)(MT <= 2 ? NS - 1 : NS) * MT * 16 * 17 + (MT <= 2 ? 4 * 128 : 0)) * sizeof(uint4);
     allow_lds(gemm_skinny_kernel<MT, 1, GROUPED, NS>, smem);
     TS_LAUNCH("gemm_skinny", (gemm_skinny_kernel<MT, 1, GROUPED, NS>), grid, dim3(256), smem, s, a);
   }

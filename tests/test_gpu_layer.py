@@ -209,6 +209,7 @@ def _pipeline_case(B, wl, weights, io, n_mb, mask):
     host = torch.zeros(max(stride * n_mb, 16), dtype=torch.uint8).pin_memory()
     half = (B.ts_layer_workspace_bytes(desc, per, per) + 255) // 256 * 256
     ws = torch.zeros(2 * half, dtype=torch.uint8, device=DEV)
+    ws_wide = torch.zeros(n_mb * half, dtype=torch.uint8, device=DEV)
     pipe = B.ts_pipeline_create(desc, n_mb)
     streams = [torch.cuda.Stream(), torch.cuda.Stream()]
     copy = torch.cuda.Stream()
@@ -219,7 +220,10 @@ def _pipeline_case(B, wl, weights, io, n_mb, mask):
     delta_host = torch.zeros(dstride * n_mb, dtype=torch.uint8).pin_memory()
     torch.cuda.synchronize()
     try:
-        for rep in range(3):       # later repetitions reuse staging slots and workspace halves; the last coalesces sends
+        # later repetitions reuse staging slots and workspace slots; the third coalesces sends at four points of
+        # the layer, the fourth at two, the fifth gets a workspace slot per micro-batch (another slot geometry
+        # than the step before it, so it waits for all of that step's transfers)
+        for rep in range(5):
             # the KV delta is replicated in the background from the second repetition on
             if rep >= 1:
                 B.ts_pipeline_set_kv_delta(pipe, delta_stream, delta_dev, delta_host)
@@ -230,8 +234,9 @@ def _pipeline_case(B, wl, weights, io, n_mb, mask):
             caches = [{k: v.clone() for k, v in ios_dev[i].items()} for i in range(n_mb)]
             mbs = [B.make_io(caches[i], outs[i], per, per) for i in range(n_mb)]
             host.zero_()
-            B.ts_pipeline_step(pipe, wts, mbs, streams, copy, mask, staging, host, ws,
-                               copy_mode=B.TS_PIPE_COPY_COALESCED if rep == 2 else B.TS_PIPE_COPY_SIDE_STREAM)
+            mode = {2: B.TS_PIPE_COPY_COALESCED, 3: B.TS_PIPE_COPY_COALESCED_HALVES}.get(rep, B.TS_PIPE_COPY_SIDE_STREAM)
+            B.ts_pipeline_step(pipe, wts, mbs, streams, copy, mask, staging, host, ws_wide if rep == 4 else ws,
+                               copy_mode=mode)
             for st in streams + [copy, delta_stream]:
                 st.synchronize()
             if rep >= 1:
