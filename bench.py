@@ -25,10 +25,11 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16, published
-# What the same chip sustains in the two calibration microbenchmarks (a plain linear read of 34 MB - 940 MB;
-# a register-resident 32x32x16 bf16 MFMA loop on 8 waves per CU): reported beside the published peaks.
-HBM_CALIBRATED_GBS = 5900.0
-MFMA_BF16_CALIBRATED_TFLOPS = 2400.0
+# What the same chip sustains in the two calibration microbenchmarks (a pure read of 1 GiB with whole-line,
+# non-temporal 16-byte loads: 7.0-7.1 TB/s, against 5.9-6.4 with plain loads; a register-resident bf16 MFMA
+# loop on 8 waves per CU with zero operands: 2.44-2.47 PFLOP/s): reported beside the published peaks.
+HBM_CALIBRATED_GBS = 7000.0
+MFMA_BF16_CALIBRATED_TFLOPS = 2450.0
 
 
 def kernel_models(wl, lens):

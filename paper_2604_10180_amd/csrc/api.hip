@@ -42,6 +42,15 @@ struct Profile {
 };
 static thread_local Profile g_prof;
 
+static thread_local hipEvent_t g_stop_event = nullptr;
+void arm_stop_event(hipEvent_t e) { g_stop_event = e; }
+hipEvent_t take_stop_event() {
+  hipEvent_t e = g_stop_event;
+  g_stop_event = nullptr;
+  return e;
+}
+bool disarm_stop_event() { return take_stop_event() != nullptr; }
+
 void prof_begin(const char* name, hipStream_t s) {
   if (!g_prof.active || g_prof.used >= g_prof.cap) return;
   g_prof.names[g_prof.used] = name;
@@ -181,10 +190,11 @@ int validate_io(const ts_layer_desc* desc, const ts_layer_weights* w, const ts_l
   return TS_OK;
 }
 
-// The layer, with a hook invoked right after each kernel boundary has been enqueued.
-template <typename Hook>
+// The layer, with `pre(index)` invoked before the launch function whose last kernel completes boundary `index`
+// (the place to arm a stop event) and `hook(index, ptr)` right after that boundary has been enqueued.
+template <typename Pre, typename Hook>
 int layer_forward_impl(const ts_layer_desc& d, const ts_layer_weights& w, const ts_layer_io& io, char* ws,
-                       hipStream_t s, Hook&& hook) {
+                       hipStream_t s, Pre&& pre, Hook&& hook) {
   const int T = io.T, B = io.B;
   if (T == 0) return TS_OK;
   const LayerPlan p = plan_layer(d, T, B);
@@ -201,13 +211,16 @@ int layer_forward_impl(const ts_layer_desc& d, const ts_layer_weights& w, const 
   const float scale = 1.0f / sqrtf((float)d.d);
   int rc;
 #define TS_STEP(call) do { rc = (call); if (rc != TS_OK) return rc; } while (0)
+  pre(TS_B_H1);
   TS_STEP(launch_rmsnorm(io.x, w.gamma1, h1, T, d.H, d.eps, s, counters, p.counter_words));
   TS_STEP(hook(TS_B_H1, h1));
   TS_STEP(launch_gemm(h1, w.w_qkv, nullptr, qkv, false, T, nqkv, d.H, scratch, p.scratch_bytes, s));
+  pre(TS_B_QKV);
   TS_STEP(launch_rope(qkv, qkv + nqd, qkv + nqd + nkd, nqkv, nqkv, io.pos, io.seq_id, w.rope_cos_sin,
                       w.rope_cos_sin ? w.rope_table_len : 0, io.kcache, io.vcache, T, d.nq, d.nkv, d.d, d.Lcap,
                       d.rope_base, s));
   TS_STEP(hook(TS_B_QKV, qkv));
+  pre(TS_B_ATTN);
   if (d.mode == TS_MODE_DECODE) {
     TS_STEP(launch_attention_decode(qkv, nqkv, io.kcache, io.vcache, io.seq_lens, attn, B, d.nq, d.nkv, d.d, d.Lcap,
                                     scale, scratch, p.scratch_bytes, s, counters));
@@ -216,21 +229,27 @@ int layer_forward_impl(const ts_layer_desc& d, const ts_layer_weights& w, const 
                                      io.max_seqlen, d.nq, d.nkv, d.d, scale, 1, s));
   }
   TS_STEP(hook(TS_B_ATTN, attn));
+  pre(TS_B_X2);
   TS_STEP(launch_gemm(attn, w.w_o, io.x, x2, false, T, d.H, nqd, scratch, p.scratch_bytes, s));
   TS_STEP(hook(TS_B_X2, x2));
+  pre(TS_B_H2);
   TS_STEP(launch_rmsnorm(x2, w.gamma2, h2, T, d.H, d.eps, s));
   TS_STEP(hook(TS_B_H2, h2));
   if (d.E == 0) {
     if (gemm_mfma256_glu_supported(T, d.F, d.H)) {
       // MFMA-bound sizes: the activation is applied in the projection's epilogue (both tensors are still written)
+      pre(TS_B_GATE_UP);
       TS_STEP(launch_gemm_mfma256_glu(h2, w.w_gate_up, gate_up, act, T, d.F, d.H, s));
       TS_STEP(hook(TS_B_GATE_UP, gate_up));
     } else {
+      pre(TS_B_GATE_UP);
       TS_STEP(launch_gemm(h2, w.w_gate_up, nullptr, gate_up, false, T, 2 * d.F, d.H, scratch, p.scratch_bytes, s));
       TS_STEP(hook(TS_B_GATE_UP, gate_up));
+      pre(TS_B_ACT);
       TS_STEP(launch_swiglu(gate_up, act, T, d.F, s));
     }
     TS_STEP(hook(TS_B_ACT, act));
+    pre(TS_B_OUT_DENSE);
     TS_STEP(launch_gemm(act, w.w_down, x2, io.out, false, T, d.H, d.F, scratch, p.scratch_bytes, s));
     TS_STEP(hook(TS_B_OUT_DENSE, io.out));
   } else {
@@ -248,12 +267,16 @@ int layer_forward_impl(const ts_layer_desc& d, const ts_layer_weights& w, const 
     else
       TS_STEP(launch_gemm(h2, w.w_router, nullptr, logits, true, T, d.E, d.H, scratch, p.scratch_bytes, s));
     TS_STEP(launch_moe_route(logits, T, d.E, d.k, tidx, tw, counts, offs, perm, s));
+    pre(TS_B_GATE_UP);
     TS_STEP(launch_moe_gemm(h2, perm, d.k, w.w_gate_up, offs, gate_up, rows, d.E, 2 * d.F, d.H, s));
     TS_STEP(hook(TS_B_GATE_UP, gate_up));
+    pre(TS_B_ACT);
     TS_STEP(launch_swiglu(gate_up, act, rows, d.F, s));
     TS_STEP(hook(TS_B_ACT, act));
+    pre(TS_B_Y_MOE);
     TS_STEP(launch_moe_gemm(act, nullptr, 1, w.w_down, offs, y, rows, d.E, d.H, d.F, s));
     TS_STEP(hook(TS_B_Y_MOE, y));
+    pre(TS_B_OUT_MOE);
     TS_STEP(launch_moe_combine(y, perm, tw, x2, io.out, inv, T, d.k, d.H, s));
     TS_STEP(hook(TS_B_OUT_MOE, io.out));
   }
@@ -475,7 +498,7 @@ int ts_layer_forward(const ts_layer_desc* desc, const ts_layer_weights* w, const
   TS_REQUIRE(io->T == 0 || (ws != nullptr && ws_bytes >= need), TS_ERR_WORKSPACE,
              "ts_layer_forward: workspace %zu bytes < required %zu", ws_bytes, need);
   TS_REQUIRE(aligned16(ws), TS_ERR_INVALID_ARG, "ts_layer_forward: workspace not 16-byte aligned");
-  return layer_forward_impl(*desc, *w, *io, reinterpret_cast<char*>(ws), as_stream(stream),
+  return layer_forward_impl(*desc, *w, *io, reinterpret_cast<char*>(ws), as_stream(stream), [](int) {},
                             [](int, const void*) { return TS_OK; });
 }
 
@@ -651,16 +674,33 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
     const bool coalesce = copy_mode == TS_PIPE_COPY_COALESCED || halves;
     const bool serial = copy_mode == TS_PIPE_COPY_SERIALISED;
     // send what is pending: one event on the compute stream, one pack launch on the copy stream
+    // a send point: on coalesced sends the designated boundaries and the end of the layer
+    auto send_point = [&](int index) {
+      if (halves) return index == TS_B_X2 || index == nb - 1;
+      return index == TS_B_QKV || index == TS_B_H2 || index == TS_B_ACT || index == nb - 1;
+    };
+    // Before the launch function that completes boundary `index`: if a send will follow it, let its last
+    // kernel carry the boundary's event (fires when the kernel completes; no marker packet on the compute
+    // stream).  `attached` tells the hook whether a kernel took it.
+    bool armed = false, attached = false;
+    auto pre = [&](int index) {
+      const bool flagged = (boundary_mask >> index) & 1;
+      armed = !serial && (coalesce ? send_point(index) && (flagged || pending.n > 0) : flagged);
+      if (armed) arm_stop_event(p->boundary_ev[(size_t)i * TS_NB_MOE + index]);
+    };
     auto flush = [&](int index) -> int {
       if (pending.n == 0) return TS_OK;
       hipEvent_t e = p->boundary_ev[(size_t)i * TS_NB_MOE + index];
-      TS_HIP(hipEventRecord(e, s));
+      if (!attached) TS_HIP(hipEventRecord(e, s));
       TS_HIP(hipStreamWaitEvent(copy, e, 0));
       int rc2 = launch_copy16_multi(pending, slot_dev, slot_host, copy);
       pending.n = 0;
       return rc2;
     };
     auto hook = [&](int index, const void* ptr) -> int {
+      attached = armed && !disarm_stop_event();   // armed and no longer pending: a kernel carries the event
+      if (!armed) disarm_stop_event();
+      armed = false;
       if (index == TS_B_QKV && p->delta_on) {
         // the K and V rows this step appends to the cache are columns [nq d, (nq + 2 nkv) d) of the projection
         // buffer: one strided pack on the delta stream, behind an event of its own
@@ -686,7 +726,7 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
           hipStream_t target = s;
           if (!serial) {
             hipEvent_t e = p->boundary_ev[(size_t)i * TS_NB_MOE + index];
-            TS_HIP(hipEventRecord(e, s));
+            if (!attached) TS_HIP(hipEventRecord(e, s));
             TS_HIP(hipStreamWaitEvent(copy, e, 0));
             target = copy;
           }
@@ -697,11 +737,11 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
       // coalesced sends leave after RoPE, after the second norm, after SwiGLU and at the end of the layer (the
       // last one is then only the layer output: the next user of this workspace half waits for it)
       // (TS_PIPE_COPY_COALESCED_HALVES: after the attention half of the layer and at the end)
-      const bool at_point = halves ? index == TS_B_X2 : (index == TS_B_QKV || index == TS_B_H2 || index == TS_B_ACT);
-      if (coalesce && (at_point || index == nb - 1 || pending.n == 4)) return flush(index);
+      if (coalesce && (send_point(index) || pending.n == 4)) return flush(index);
       return TS_OK;
     };
-    rc = layer_forward_impl(d, *w, mb[i], wsh, s, hook);
+    rc = layer_forward_impl(d, *w, mb[i], wsh, s, pre, hook);
+    disarm_stop_event();
     if (rc != TS_OK) return rc;
     if (boundary_mask != 0 && copy_mode != TS_PIPE_COPY_SERIALISED) TS_HIP(hipEventRecord(p->packed_ev[i], copy));
   }

@@ -342,20 +342,20 @@ int launch_attention_decode(const ts_bf16* q, int q_stride, const ts_bf16* kc, c
     const size_t stage = (size_t)4 * kBlockKeys * 17 * sizeof(uint4);
     const size_t merge = (size_t)(4 * 16 * 128 + 128) * sizeof(float);
     const size_t smem = stage > merge ? stage : merge;
-    TS_LAUNCH("attn_decode_split", attn_decode_split_kernel<128>, grid, dim3(256), smem, s, q, kc, vc, seq_lens, part, q_stride, nq,
+    TS_LAUNCH_EX(!merge_kernel, "attn_decode_split", attn_decode_split_kernel<128>, grid, dim3(256), smem, s, q, kc, vc, seq_lens, part, q_stride, nq,
                        nkv, Lcap, NCH, plan.chunk_target, c_scale, counters, out);
     TS_LAUNCH_CHECK("attn_decode_split");
     if (merge_kernel)
-      TS_LAUNCH("attn_decode_merge", attn_decode_merge_kernel<128>, dim3(B * nq), dim3(128), 0, s, part, seq_lens, out, nq, NCH, plan.chunk_target);
+      TS_LAUNCH_LAST("attn_decode_merge", attn_decode_merge_kernel<128>, dim3(B * nq), dim3(128), 0, s, part, seq_lens, out, nq, NCH, plan.chunk_target);
   } else {
     const size_t stage = (size_t)4 * kBlockKeys * 9 * sizeof(uint4);
     const size_t merge = (size_t)(4 * 16 * 64 + 128) * sizeof(float);
     const size_t smem = stage > merge ? stage : merge;
-    TS_LAUNCH("attn_decode_split", attn_decode_split_kernel<64>, grid, dim3(256), smem, s, q, kc, vc, seq_lens, part, q_stride, nq,
+    TS_LAUNCH_EX(!merge_kernel, "attn_decode_split", attn_decode_split_kernel<64>, grid, dim3(256), smem, s, q, kc, vc, seq_lens, part, q_stride, nq,
                        nkv, Lcap, NCH, plan.chunk_target, c_scale, counters, out);
     TS_LAUNCH_CHECK("attn_decode_split");
     if (merge_kernel)
-      TS_LAUNCH("attn_decode_merge", attn_decode_merge_kernel<64>, dim3(B * nq), dim3(64), 0, s, part, seq_lens, out, nq, NCH, plan.chunk_target);
+      TS_LAUNCH_LAST("attn_decode_merge", attn_decode_merge_kernel<64>, dim3(B * nq), dim3(64), 0, s, part, seq_lens, out, nq, NCH, plan.chunk_target);
   }
   TS_LAUNCH_CHECK("attn_decode_merge");
   return TS_OK;

@@ -340,7 +340,7 @@ int launch_attention_prefill(const ts_bf16* q, const ts_bf16* k, const ts_bf16* 
   const int nqb = cdiv(max_seqlen, QB);
   dim3 grid(nqb * nkv * (group / hpw) * S);
 #define TS_PREFILL_LAUNCH(kern, threads) \
-  TS_LAUNCH("attn_prefill", kern, grid, dim3(threads), 0, s, q, k, v, q_stride, kv_stride, cu, out, nq, nkv, hpw, S, nqb, c_scale, causal)
+  TS_LAUNCH_LAST("attn_prefill", kern, grid, dim3(threads), 0, s, q, k, v, q_stride, kv_stride, cu, out, nq, nkv, hpw, S, nqb, c_scale, causal)
   if (d == 128) TS_PREFILL_LAUNCH(attn_prefill_d128_w4_kernel, 256);
   else TS_PREFILL_LAUNCH(attn_prefill_d64_w4_kernel, 256);
   TS_LAUNCH_CHECK("attn_prefill");

@@ -64,11 +64,11 @@ int launch_rmsnorm(const ts_bf16* x, const ts_bf16* gamma, ts_bf16* y, int T, in
   const uint4* gp = reinterpret_cast<const uint4*>(gamma);
   uint4* yp = reinterpret_cast<uint4*>(y);
   const float inv_h = 1.0f / (float)H;
-  if (vpt <= 1) TS_LAUNCH("rmsnorm", rmsnorm_kernel<1>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero);
-  else if (vpt <= 2) TS_LAUNCH("rmsnorm", rmsnorm_kernel<2>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero);
-  else if (vpt <= 4) TS_LAUNCH("rmsnorm", rmsnorm_kernel<4>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero);
-  else if (vpt <= 8) TS_LAUNCH("rmsnorm", rmsnorm_kernel<8>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero);
-  else TS_LAUNCH("rmsnorm", rmsnorm_kernel<16>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero);
+  if (vpt <= 1) TS_LAUNCH_LAST("rmsnorm", rmsnorm_kernel<1>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero);
+  else if (vpt <= 2) TS_LAUNCH_LAST("rmsnorm", rmsnorm_kernel<2>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero);
+  else if (vpt <= 4) TS_LAUNCH_LAST("rmsnorm", rmsnorm_kernel<4>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero);
+  else if (vpt <= 8) TS_LAUNCH_LAST("rmsnorm", rmsnorm_kernel<8>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero);
+  else TS_LAUNCH_LAST("rmsnorm", rmsnorm_kernel<16>, grid, block, 0, s, xp, gp, yp, H8, eps, inv_h, zero, nzero);
   TS_LAUNCH_CHECK("rmsnorm");
   return TS_OK;
 }
@@ -99,7 +99,7 @@ int launch_swiglu(const ts_bf16* gu, ts_bf16* out, int T, int F, hipStream_t s) 
   const int F8 = F / 8;
   long total = (long)T * F8;
   dim3 grid((unsigned)((total + 255) / 256)), block(256);
-  TS_LAUNCH("swiglu", swiglu_kernel, grid, block, 0, s, reinterpret_cast<const uint4*>(gu),
+  TS_LAUNCH_LAST("swiglu", swiglu_kernel, grid, block, 0, s, reinterpret_cast<const uint4*>(gu),
                      reinterpret_cast<uint4*>(out), total, F8);
   TS_LAUNCH_CHECK("swiglu");
   return TS_OK;
@@ -179,7 +179,7 @@ int launch_rope(ts_bf16* q, ts_bf16* k, const ts_bf16* v, int q_stride, int kv_s
   if (T == 0) return TS_OK;
   const int items = (nq + nkv) * (d / 16) + (vcache ? nkv * (d / 8) : 0);
   dim3 grid(cdiv(items, 256), T), block(256);
-  TS_LAUNCH("rope", rope_kernel, grid, block, 0, s, q, k, v, q_stride, kv_stride, pos, seq_id, cos_sin, table_len,
+  TS_LAUNCH_LAST("rope", rope_kernel, grid, block, 0, s, q, k, v, q_stride, kv_stride, pos, seq_id, cos_sin, table_len,
                      kcache, vcache, nq, nkv, d, Lcap, base);
   TS_LAUNCH_CHECK("rope");
   return TS_OK;

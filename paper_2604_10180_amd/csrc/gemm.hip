@@ -567,7 +567,7 @@ void launch_skinny_mt(const SkinnyArgs& a, int NT, dim3 grid, hipStream_t s, int
         constexpr int NS = skinny_stages<MT, NTc>();
         const size_t smem = ((size_t)(MT <= 2 ? NS - 1 : NS) * MT * 16 * 17 + (MT <= 2 ? Wc * 128 : 0)) * sizeof(uint4);
         allow_lds(gemm_skinny_kernel<MT, NTc, GROUPED, NS, Wc>, smem);
-        TS_LAUNCH("gemm_skinny", (gemm_skinny_kernel<MT, NTc, GROUPED, NS, Wc>), grid, dim3(64 * Wc), smem, s, a);
+        TS_LAUNCH_EX(a.S == 1, "gemm_skinny", (gemm_skinny_kernel<MT, NTc, GROUPED, NS, Wc>), grid, dim3(64 * Wc), smem, s, a);
       };
       using I1 = std::integral_constant<int, 1>;
       using I2 = std::integral_constant<int, 2>;
@@ -582,12 +582,12 @@ void launch_skinny_mt(const SkinnyArgs& a, int NT, dim3 grid, hipStream_t s, int
     constexpr int NS = skinny_stages<MT, 2>();
     const size_t smem = ((size_t)(MT <= 2 ? NS - 1 : NS) * MT * 16 * 17 + (MT <= 2 ? 4 * 128 : 0)) * sizeof(uint4);
     allow_lds(gemm_skinny_kernel<MT, 2, GROUPED, NS>, smem);
-    TS_LAUNCH("gemm_skinny", (gemm_skinny_kernel<MT, 2, GROUPED, NS>), grid, dim3(256), smem, s, a);
+    TS_LAUNCH_EX(a.S == 1, "gemm_skinny", (gemm_skinny_kernel<MT, 2, GROUPED, NS>), grid, dim3(256), smem, s, a);
   } else {
     constexpr int NS = skinny_stages<MT, 1>();
     const size_t smem = ((size_t)(MT <= 2 ? NS - 1 : NS) * MT * 16 * 17 + (MT <= 2 ? 4 * 128 : 0)) * sizeof(uint4);
     allow_lds(gemm_skinny_kernel<MT, 1, GROUPED, NS>, smem);
-    TS_LAUNCH("gemm_skinny", (gemm_skinny_kernel<MT, 1, GROUPED, NS>), grid, dim3(256), smem, s, a);
+    TS_LAUNCH_EX(a.S == 1, "gemm_skinny", (gemm_skinny_kernel<MT, 1, GROUPED, NS>), grid, dim3(256), smem, s, a);
   }
 }
 
@@ -626,17 +626,17 @@ int launch_tiled(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, vo
   dim3 grid(tiles_m * tiles_n, S);
   if (f32out) {
     allow_lds(gemm_tiled_kernel<BM, BN, true>, smem);
-    TS_LAUNCH("gemm_tiled", (gemm_tiled_kernel<BM, BN, true>), grid, dim3(256), smem, s, A, W, residual, C, M, N, K,
+    TS_LAUNCH_EX(partial == nullptr, "gemm_tiled", (gemm_tiled_kernel<BM, BN, true>), grid, dim3(256), smem, s, A, W, residual, C, M, N, K,
               tiles_m, tiles_n, partial, kslice);
   } else {
     allow_lds(gemm_tiled_kernel<BM, BN, false>, smem);
-    TS_LAUNCH("gemm_tiled", (gemm_tiled_kernel<BM, BN, false>), grid, dim3(256), smem, s, A, W, residual, C, M, N, K,
+    TS_LAUNCH_EX(partial == nullptr, "gemm_tiled", (gemm_tiled_kernel<BM, BN, false>), grid, dim3(256), smem, s, A, W, residual, C, M, N, K,
               tiles_m, tiles_n, partial, kslice);
   }
   TS_LAUNCH_CHECK("gemm_tiled");
   if (partial != nullptr) {
     const long MN = (long)M * N;
-    TS_LAUNCH("splitk_reduce", splitk_reduce_kernel, dim3((unsigned)((MN / 2 + 255) / 256)), dim3(256), 0, s, partial,
+    TS_LAUNCH_LAST("splitk_reduce", splitk_reduce_kernel, dim3((unsigned)((MN / 2 + 255) / 256)), dim3(256), 0, s, partial,
               residual, C, MN, S, f32out ? 1 : 0);
     TS_LAUNCH_CHECK("splitk_reduce");
   }
@@ -674,7 +674,7 @@ int launch_gemm(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, voi
     TS_LAUNCH_CHECK("gemm_skinny");
     if (p.S > 1) {
       long MN = (long)M * N;
-      TS_LAUNCH("splitk_reduce", splitk_reduce_kernel, dim3((unsigned)((MN / 2 + 255) / 256)), dim3(256), 0, s,
+      TS_LAUNCH_LAST("splitk_reduce", splitk_reduce_kernel, dim3((unsigned)((MN / 2 + 255) / 256)), dim3(256), 0, s,
                          reinterpret_cast<const float*>(ws), residual, C, MN, p.S, f32out ? 1 : 0);
       TS_LAUNCH_CHECK("splitk_reduce");
     }

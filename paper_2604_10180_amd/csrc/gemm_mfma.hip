@@ -356,7 +356,7 @@ bool gemm_mfma256_glu_supported(int M, int F, int K) {
 int launch_gemm_mfma256_glu(const ts_bf16* A, const ts_bf16* W, ts_bf16* gate_up, ts_bf16* act, int M, int F, int K,
                             hipStream_t s) {
   const int tiles_m = cdiv(M, kTile), tiles_n = F / 128;
-  TS_LAUNCH("gemm_mfma256_glu", gemm_mfma256_glu_kernel, dim3(tiles_m * tiles_n), dim3(512), 0, s, A, W, gate_up, act, M,
+  TS_LAUNCH_LAST("gemm_mfma256_glu", gemm_mfma256_glu_kernel, dim3(tiles_m * tiles_n), dim3(512), 0, s, A, W, gate_up, act, M,
             2 * F, K, tiles_m, tiles_n);
   TS_LAUNCH_CHECK("gemm_mfma256_glu");
   return TS_OK;
@@ -365,7 +365,7 @@ int launch_gemm_mfma256_glu(const ts_bf16* A, const ts_bf16* W, ts_bf16* gate_up
 int launch_gemm_mfma256(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, ts_bf16* C, int M, int N, int K,
                         hipStream_t s) {
   const int tiles_m = cdiv(M, kTile), tiles_n = cdiv(N, kTile);
-  TS_LAUNCH("gemm_mfma256", gemm_mfma256_kernel, dim3(tiles_m * tiles_n), dim3(512), 0, s, A, W, residual, C, M, N, K,
+  TS_LAUNCH_LAST("gemm_mfma256", gemm_mfma256_kernel, dim3(tiles_m * tiles_n), dim3(512), 0, s, A, W, residual, C, M, N, K,
             tiles_m, tiles_n);
   TS_LAUNCH_CHECK("gemm_mfma256");
   return TS_OK;

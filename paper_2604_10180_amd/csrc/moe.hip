@@ -189,7 +189,7 @@ int launch_moe_combine(const ts_bf16* y, const int32_t* perm, const float* w, co
   TS_LAUNCH_CHECK("moe_invert");
   const int H8 = H / 8;
   long total = (long)T * H8;
-  TS_LAUNCH("moe_combine", moe_combine_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
+  TS_LAUNCH_LAST("moe_combine", moe_combine_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s,
                      reinterpret_cast<const uint4*>(y), inv, w, reinterpret_cast<const uint4*>(residual),
                      reinterpret_cast<uint4*>(out), total, H8, k);
   TS_LAUNCH_CHECK("moe_combine");
