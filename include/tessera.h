@@ -284,11 +284,11 @@ int ts_layer_forward(const ts_layer_desc* desc, const ts_layer_weights* w, const
  * All micro-batches must flag the same boundaries; their T may differ (the
  * layout is computed for each T; slot_stride uses the largest).
  * copy_mode: TS_PIPE_COPY_SIDE_STREAM sends every flagged boundary as soon as its kernel is enqueued (one
- * event on the compute stream per boundary); TS_PIPE_COPY_SERIALISED runs the pack kernels on the compute
+ * event per boundary, carried by the kernel that completes it); TS_PIPE_COPY_SERIALISED runs the pack kernels on the compute
  * stream itself (the no-overlap reference); TS_PIPE_COPY_COALESCED sends on the side stream at four
  * points of the layer (after RoPE, after the second norm, after SwiGLU, at the end), each send carrying
- * the flagged boundaries produced since the previous one: half the events between the compute kernels
- * (an event costs the compute stream about 2 us), same bytes in the same slots.
+ * the flagged boundaries produced since the previous one: half the events and pack launches, same bytes in
+ * the same slots.
  * TS_PIPE_COPY_COALESCED_HALVES sends twice per layer (after the attention half, i.e. once x2 exists, and
  * at the end; a send carries at most four tensors, so a layer with more than eight boundaries sends a third
  * time): a quarter of the events.  A boundary then leaves up to half a layer after it was produced, which

@@ -703,9 +703,11 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
       armed = false;
       if (index == TS_B_QKV && p->delta_on) {
         // the K and V rows this step appends to the cache are columns [nq d, (nq + 2 nkv) d) of the projection
-        // buffer: one strided pack on the delta stream, behind an event of its own
-        TS_HIP(hipEventRecord(p->kv_ready_ev[i], s));
-        TS_HIP(hipStreamWaitEvent(p->delta_stream, p->kv_ready_ev[i], 0));
+        // buffer: one strided pack on the delta stream
+        // (the boundary's own event if the RoPE kernel carries it)
+        hipEvent_t ready = attached ? p->boundary_ev[(size_t)i * TS_NB_MOE + index] : p->kv_ready_ev[i];
+        if (!attached) TS_HIP(hipEventRecord(ready, s));
+        TS_HIP(hipStreamWaitEvent(p->delta_stream, ready, 0));
         const int nqkv = (d.nq + 2 * d.nkv) * d.d;
         int rc2 = launch_copy_rows(reinterpret_cast<const ts_bf16*>(ptr) + (size_t)d.nq * d.d, (size_t)nqkv * sizeof(ts_bf16),
                                    (size_t)2 * d.nkv * d.d * sizeof(ts_bf16), mb[i].T, p->delta_dev + (size_t)i * dstride,
