@@ -118,6 +118,7 @@ GEMM_SHAPES = [
     (256, 6144, 4096), (200, 1002, 1544),                   # 128 x 128 tiles split along K (reduce kernel), with tails
     (4096, 4096, 128), (3900, 4104, 192), (3585, 3592, 64),  # 256 x 256 direct-to-LDS kernel: even/odd K steps, ragged M and N
     (8, 8200, 4096), (33, 28674, 520), (64, 28672, 1024),   # seven- and eight-wave streaming workgroups: N tails, K tail, no split
+    (32, 4104, 1160), (16, 2056, 136), (24, 130, 8),        # weights staged through LDS (up to 32 rows): N and K tails, K < one chunk row
 ]
 
 
