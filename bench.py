@@ -227,6 +227,39 @@ def time_pipeline(B, torch, wl, desc, dev_set, io_cpu, dev, steps, warmup, extra
         out["kv_delta_bytes_per_step"] = int(per * 2 * s.nkv * s.d * 2 * n_mb)
     finally:
         B.ts_pipeline_destroy(pipe)
+    # Interconnect sensitivity (Sec. 5: 200 down to 25 Gbps): every boundary crosses the host link `factor` times,
+    # coalesced sends.  The link's own rate is read off the largest factor, where the step is link-bound.
+    pipe = B.ts_pipeline_create(desc, n_mb)
+    try:
+        # all boundaries (stress), and the two edges that are cut when only the attention kernel runs elsewhere
+        # (its input, the rotated projections, and its output)
+        attn_cut = (1 << B.TS_B_QKV) | (1 << B.TS_B_ATTN)
+        sweeps = {}
+        for label, mask in (("all_boundaries", full), ("attention_cut", attn_cut)):
+            sweep = []
+            for factor in (1, 2, 4, 8, 16):
+                B.ts_pipeline_set_link_slowdown(pipe, factor)
+                def one_slow():
+                    B.ts_pipeline_step(pipe, wts, mbs, streams, copy, mask, staging, host, ws, copy_mode=B.TS_PIPE_COPY_COALESCED)
+                for _ in range(max(2, warmup // 2)):
+                    one_slow()
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                for _ in range(max(5, steps // 2)):
+                    one_slow()
+                torch.cuda.synchronize()
+                sweep.append({"factor": factor, "ms": round((time.perf_counter() - t0) * 1e3 / max(5, steps // 2), 4)})
+            sweeps[label] = {"bytes_per_step": int(B.ts_pipeline_slot_stride(desc, per, per, mask) * n_mb), "steps": sweep}
+        last = sweeps["all_boundaries"]["steps"][-1]
+        link_gbs = sweeps["all_boundaries"]["bytes_per_step"] * last["factor"] / (last["ms"] * 1e-3) / 1e9
+        for sw in sweeps.values():
+            for e in sw["steps"]:
+                e["emulated_link_GBps"] = round(link_gbs / e["factor"], 2)
+                e["vs_no_copies"] = round(e["ms"] / out["no_copies_ms"], 4)
+        out["link_sweep"] = {"host_link_GBps": round(link_gbs, 2),
+                             "link_bound_at_largest_factor": last["ms"] > 1.5 * out["no_copies_ms"], **sweeps}
+    finally:
+        B.ts_pipeline_destroy(pipe)
     out["tokens_per_s_side_stream"] = round(wl.B / (out["side_stream_ms"] * 1e-3), 1)
     out["overlap_ratio"] = round(out["side_stream_ms"] / out["no_copies_ms"], 4)
     out["overlap_ratio_coalesced"] = round(out["coalesced_ms"] / out["no_copies_ms"], 4)

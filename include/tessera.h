@@ -319,6 +319,12 @@ size_t ts_pipeline_slot_stride(const ts_layer_desc* desc, int T, int B, uint64_t
 size_t ts_pipeline_kv_delta_stride(const ts_layer_desc* desc, int T);
 int ts_pipeline_set_kv_delta(ts_pipeline* p, void* delta_stream, void* dev_slots, void* host_slots,
                              size_t bytes);
+/* Slower link (Sec. 5, sensitivity of the method to the interconnect bandwidth: 200 down to 25 Gbps): from the
+ * next step on every boundary tensor is stored `factor` times to its pinned-host slot, so the bytes that
+ * cross the host link are multiplied and the link looks `factor` times slower to the step; slot contents and
+ * everything on the device are unchanged.  factor in [1,64], 1 = off (default).  Host; TS_ERR_INVALID_ARG
+ * otherwise.  The KV delta stream is not affected. */
+int ts_pipeline_set_link_slowdown(ts_pipeline* p, int factor);
 int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_io* mb, int n_mb,
                      void* compute_streams[2], void* copy_stream, uint64_t boundary_mask,
                      int copy_mode, void* dev_staging, void* pinned_host,

@@ -26,7 +26,7 @@ EXPORTS = [
     "ts_attention_decode", "ts_attention_prefill", "ts_swiglu", "ts_moe_route", "ts_moe_gemm", "ts_moe_combine",
     "ts_layer_workspace_bytes", "ts_layer_boundary", "ts_layer_moe_buffers", "ts_layer_forward",
     "ts_pipeline_create", "ts_pipeline_destroy", "ts_pipeline_boundary_layout", "ts_pipeline_slot_stride",
-    "ts_pipeline_step", "ts_pipeline_kv_delta_stride", "ts_pipeline_set_kv_delta", "ts_ddg_build", "ts_layer_ddg", "ts_layer_node_name", "ts_layer_cut_mask", "ts_plan_policy", "ts_plan_lower_bound",
+    "ts_pipeline_step", "ts_pipeline_kv_delta_stride", "ts_pipeline_set_kv_delta", "ts_pipeline_set_link_slowdown", "ts_ddg_build", "ts_layer_ddg", "ts_layer_node_name", "ts_layer_cut_mask", "ts_plan_policy", "ts_plan_lower_bound",
     "ts_monitor_create", "ts_monitor_destroy", "ts_monitor_record", "ts_monitor_advance",
 ]
 
@@ -122,6 +122,7 @@ lib.ts_pipeline_boundary_layout.argtypes = [C.POINTER(LayerDesc), _i, _i, _u64, 
 lib.ts_pipeline_slot_stride.argtypes = [C.POINTER(LayerDesc), _i, _i, _u64]
 lib.ts_pipeline_kv_delta_stride.argtypes = [C.POINTER(LayerDesc), _i]
 lib.ts_pipeline_set_kv_delta.argtypes = [_p, _p, _p, _p, _z]
+lib.ts_pipeline_set_link_slowdown.argtypes = [_p, C.c_int]
 lib.ts_pipeline_step.argtypes = [_p, C.POINTER(LayerWeights), C.POINTER(LayerIO), _i, C.POINTER(_p), _p, _u64, _i,
                                  _p, _p, _z, _p, _z]
 lib.ts_ddg_build.argtypes = [C.POINTER(KernelIO), _i, C.POINTER(DdgEdge), _i, C.POINTER(_i)]
@@ -311,6 +312,10 @@ def ts_pipeline_set_kv_delta(handle: int, delta_stream, dev_slots, host_slots) -
         return
     _check(lib.ts_pipeline_set_kv_delta(handle, _stream(delta_stream), _ptr(dev_slots), _ptr(host_slots),
                                         min(_nbytes(dev_slots), _nbytes(host_slots))))
+
+
+def ts_pipeline_set_link_slowdown(handle: int, factor: int) -> None:
+    _check(lib.ts_pipeline_set_link_slowdown(handle, factor))
 
 
 def ts_pipeline_step(handle: int, weights: LayerWeights, mbs: Sequence[LayerIO], compute_streams, copy_stream,

@@ -521,6 +521,7 @@ struct ts_pipeline {
   std::vector<int> prev_packed, prev_kv_sent;   // [max_mb]
   size_t prev_slot_bytes = 0;
   int prev_nslot = 0;
+  int link_slowdown = 1;   // every boundary tensor crosses the host link this many times
 };
 
 int ts_pipeline_create(const ts_layer_desc* desc, int max_micro_batches, ts_pipeline** out) {
@@ -608,6 +609,14 @@ size_t ts_pipeline_slot_stride(const ts_layer_desc* desc, int T, int B, uint64_t
   return round_up(offs[n], 256);
 }
 
+int ts_pipeline_set_link_slowdown(ts_pipeline* p, int factor) {
+  TS_REQUIRE(p != nullptr, TS_ERR_INVALID_ARG, "ts_pipeline_set_link_slowdown: null pipeline");
+  TS_REQUIRE(factor >= 1 && factor <= 64, TS_ERR_INVALID_ARG, "ts_pipeline_set_link_slowdown: factor %d outside [1,64]",
+             factor);
+  p->link_slowdown = factor;
+  return TS_OK;
+}
+
 int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_io* mb, int n_mb,
                      void* compute_streams[2], void* copy_stream, uint64_t boundary_mask, int copy_mode,
                      void* dev_staging, void* pinned_host, size_t staging_bytes, void* ws, size_t ws_bytes) {
@@ -693,7 +702,7 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
       hipEvent_t e = p->boundary_ev[(size_t)i * TS_NB_MOE + index];
       if (!attached) TS_HIP(hipEventRecord(e, s));
       TS_HIP(hipStreamWaitEvent(copy, e, 0));
-      int rc2 = launch_copy16_multi(pending, slot_dev, slot_host, copy);
+      int rc2 = launch_copy16_multi(pending, slot_dev, slot_host, copy, p->link_slowdown);
       pending.n = 0;
       return rc2;
     };
@@ -733,7 +742,7 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
             target = copy;
           }
           // one kernel packs the tensor into the device slot and stores it to the pinned host slot
-          return launch_copy16(ptr, slot_dev + o, bytes, target, slot_host + o);
+          return launch_copy16(ptr, slot_dev + o, bytes, target, slot_host + o, p->link_slowdown);
         }
       }
       // coalesced sends leave after RoPE, after the second norm, after SwiGLU and at the end of the layer (the

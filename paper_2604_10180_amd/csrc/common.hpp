@@ -151,7 +151,7 @@ int launch_swiglu(const ts_bf16* gu, ts_bf16* out, int T, int F, hipStream_t s);
 int launch_rope(ts_bf16* q, ts_bf16* k, const ts_bf16* v, int q_stride, int kv_stride, const int32_t* pos,
                 const int32_t* seq_id, const float* cos_sin, int table_len, ts_bf16* kcache, ts_bf16* vcache,
                 int T, int nq, int nkv, int d, int Lcap, float base, hipStream_t s);
-int launch_copy16(const void* src, void* dst, size_t bytes, hipStream_t s, void* dst2 = nullptr);
+int launch_copy16(const void* src, void* dst, size_t bytes, hipStream_t s, void* dst2 = nullptr, int host_repeat = 1);
 // up to four tensors packed by one launch into the device slot dst and the host-mapped slot dst2
 struct CopySegments {
   const void* src[4];
@@ -159,7 +159,7 @@ struct CopySegments {
   size_t n16[4];         // length in 16-byte units
   int n;
 };
-int launch_copy16_multi(const CopySegments& segs, void* dst, void* dst2, hipStream_t s);
+int launch_copy16_multi(const CopySegments& segs, void* dst, void* dst2, hipStream_t s, int host_repeat = 1);
 int launch_copy_rows(const void* src, size_t src_stride_bytes, size_t row_bytes, int rows, void* dst, void* dst2,
                      hipStream_t s);
 

@@ -190,44 +190,54 @@ int launch_rope(ts_bf16* q, ts_bf16* k, const ts_bf16* v, int q_stride, int kv_s
 // device-mapped pinned host slot as well: the transfer is initiated by the kernel itself (the
 // analogue of the GPU-initiated sends of Sec. 4), with no copy-engine command whose cross-stream
 // dependency the runtime would resolve by blocking the launching host thread.
+// host_repeat > 1 writes the whole tensor that many times to the host slot, pass after pass (stores to one
+// address back to back would be merged on the way): the bytes over the link are multiplied, i.e. the link looks
+// that many times slower (Sec. 5, sensitivity to the interconnect bandwidth).
 __global__ __launch_bounds__(256) void copy16_kernel(const uint4* __restrict__ src, uint4* __restrict__ dst,
-                                                     uint4* __restrict__ dst2, size_t n16) {
-  size_t i = (size_t)blockIdx.x * 256 + threadIdx.x;
+                                                     uint4* __restrict__ dst2, size_t n16, int host_repeat) {
+  const size_t i0 = (size_t)blockIdx.x * 256 + threadIdx.x;
   const size_t stride = (size_t)gridDim.x * 256;
   if (dst2 == nullptr) {
-    for (; i < n16; i += stride) dst[i] = src[i];
-  } else {
-    for (; i < n16; i += stride) {
-      const uint4 v = src[i];
-      dst[i] = v;
-      dst2[i] = v;
-    }
+    for (size_t i = i0; i < n16; i += stride) dst[i] = src[i];
+    return;
+  }
+  for (size_t i = i0; i < n16; i += stride) {
+    const uint4 v = src[i];
+    dst[i] = v;
+    dst2[i] = v;
+  }
+  for (int r = 1; r < host_repeat; ++r) {
+    asm volatile("" ::: "memory");
+    for (size_t i = i0; i < n16; i += stride) dst2[i] = src[i];
   }
 }
 
 // Several boundary tensors in one launch (segments are consecutive in both destination slots).
 __global__ __launch_bounds__(256) void copy16_multi_kernel(CopySegments segs, uint4* __restrict__ dst,
-                                                           uint4* __restrict__ dst2) {
+                                                           uint4* __restrict__ dst2, int host_repeat) {
   const size_t stride = (size_t)gridDim.x * blockDim.x;
-  for (int g = 0; g < segs.n; ++g) {
-    const uint4* src = reinterpret_cast<const uint4*>(segs.src[g]);
-    const size_t base = segs.dst_off16[g], n16 = segs.n16[g];
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) {
-      const uint4 v = src[i];
-      dst[base + i] = v;
-      dst2[base + i] = v;
+  for (int r = 0; r < host_repeat; ++r) {
+    for (int g = 0; g < segs.n; ++g) {
+      const uint4* src = reinterpret_cast<const uint4*>(segs.src[g]);
+      const size_t base = segs.dst_off16[g], n16 = segs.n16[g];
+      for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) {
+        const uint4 v = src[i];
+        if (r == 0) dst[base + i] = v;
+        dst2[base + i] = v;
+      }
     }
+    asm volatile("" ::: "memory");
   }
 }
 
-int launch_copy16_multi(const CopySegments& segs, void* dst, void* dst2, hipStream_t s) {
+int launch_copy16_multi(const CopySegments& segs, void* dst, void* dst2, hipStream_t s, int host_repeat) {
   if (segs.n == 0) return TS_OK;
   // Four workgroups: the bandwidth-bound compute kernels beside it run one or two workgroups per CU and end
   // when their slowest CU ends, so every CU the pack kernel's PCIe stores sit on costs them time (measured on
   // the 70B pipelined step: 2 or 4 workgroups +4.5 % over the copy-free step, 32: +6.5 %, 512 single-wave
   // ones: +8.5 %; one workgroup cannot keep up with the step).
   TS_LAUNCH("copy16", copy16_multi_kernel, dim3(4), dim3(256), 0, s, segs, reinterpret_cast<uint4*>(dst),
-            reinterpret_cast<uint4*>(dst2));
+            reinterpret_cast<uint4*>(dst2), host_repeat);
   TS_LAUNCH_CHECK("copy16");
   return TS_OK;
 }
@@ -258,7 +268,7 @@ int launch_copy_rows(const void* src, size_t src_stride_bytes, size_t row_bytes,
   return TS_OK;
 }
 
-int launch_copy16(const void* src, void* dst, size_t bytes, hipStream_t s, void* dst2) {
+int launch_copy16(const void* src, void* dst, size_t bytes, hipStream_t s, void* dst2, int host_repeat) {
   if (bytes == 0) return TS_OK;
   size_t n16 = bytes / 16;
   unsigned blocks = (unsigned)((n16 + 255) / 256);
@@ -266,7 +276,7 @@ int launch_copy16(const void* src, void* dst, size_t bytes, hipStream_t s, void*
   const unsigned cap = dst2 != nullptr ? 4 : 2048;
   if (blocks > cap) blocks = cap;
   TS_LAUNCH("copy16", copy16_kernel, dim3(blocks), dim3(256), 0, s, reinterpret_cast<const uint4*>(src),
-            reinterpret_cast<uint4*>(dst), reinterpret_cast<uint4*>(dst2), n16);
+            reinterpret_cast<uint4*>(dst), reinterpret_cast<uint4*>(dst2), n16, host_repeat);
   TS_LAUNCH_CHECK("copy16");
   return TS_OK;
 }

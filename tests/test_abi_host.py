@@ -56,6 +56,9 @@ def test_argument_errors_without_gpu(B):
     with pytest.raises(B.TesseraError) as e:
         B.ts_moe_route(16, 4, 8, 9, 16, 16, 16, 16, 16, stream=0)                      # k > E
     assert e.value.code == B.TS_ERR_INVALID_ARG
+    with pytest.raises(B.TesseraError) as e:
+        B.ts_pipeline_set_link_slowdown(None, 2)                                        # no pipeline
+    assert e.value.code == B.TS_ERR_INVALID_ARG
     # T == 0 is a no-op that never reaches the GPU
     B.ts_rmsnorm(None, None, None, 0, 256, 1e-5, stream=0)
     B.ts_swiglu(None, None, 0, 64, stream=0)

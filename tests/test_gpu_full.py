@@ -317,3 +317,10 @@ def test_70b_pipeline_boundary_copies_overlap(B):
     assert r["side_stream_ms"] <= 1.03 * r["serialised_ms"], r
     assert r["coalesced_ms"] <= 1.08 * r["no_copies_ms"], r
     assert r["coalesced_ms"] <= 1.03 * r["serialised_ms"], r
+    # Sec. 5, interconnect sensitivity: with only the attention kernel's two edges cut, a link sixteen times
+    # slower (about the 25 Gbps of the paper's sweep) still hides behind the other micro-batches; with every
+    # boundary crossing it the step becomes link-bound
+    sweep = r["link_sweep"]
+    assert sweep["attention_cut"]["steps"][-1]["factor"] == 16
+    assert sweep["attention_cut"]["steps"][-1]["vs_no_copies"] <= 1.10, sweep
+    assert sweep["all_boundaries"]["steps"][-1]["ms"] > sweep["all_boundaries"]["steps"][0]["ms"] * 1.3, sweep

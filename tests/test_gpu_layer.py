@@ -223,7 +223,8 @@ def _pipeline_case(B, wl, weights, io, n_mb, mask):
         # later repetitions reuse staging slots and workspace slots; the third coalesces sends at four points of
         # the layer, the fourth at two, the fifth gets a workspace slot per micro-batch (another slot geometry
         # than the step before it, so it waits for all of that step's transfers)
-        for rep in range(5):
+        # the sixth crosses the host link three times per tensor (slower-link emulation): same bytes in the slots
+        for rep in range(6):
             # the KV delta is replicated in the background from the second repetition on
             if rep >= 1:
                 B.ts_pipeline_set_kv_delta(pipe, delta_stream, delta_dev, delta_host)
@@ -234,7 +235,12 @@ def _pipeline_case(B, wl, weights, io, n_mb, mask):
             caches = [{k: v.clone() for k, v in ios_dev[i].items()} for i in range(n_mb)]
             mbs = [B.make_io(caches[i], outs[i], per, per) for i in range(n_mb)]
             host.zero_()
-            mode = {2: B.TS_PIPE_COPY_COALESCED, 3: B.TS_PIPE_COPY_COALESCED_HALVES}.get(rep, B.TS_PIPE_COPY_SIDE_STREAM)
+            mode = {2: B.TS_PIPE_COPY_COALESCED, 3: B.TS_PIPE_COPY_COALESCED_HALVES,
+                    5: B.TS_PIPE_COPY_COALESCED}.get(rep, B.TS_PIPE_COPY_SIDE_STREAM)
+            if rep == 5:
+                with pytest.raises(B.TesseraError):
+                    B.ts_pipeline_set_link_slowdown(pipe, 0)
+                B.ts_pipeline_set_link_slowdown(pipe, 3)
             B.ts_pipeline_step(pipe, wts, mbs, streams, copy, mask, staging, host, ws_wide if rep == 4 else ws,
                                copy_mode=mode)
             for st in streams + [copy, delta_stream]:
