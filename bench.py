@@ -481,8 +481,13 @@ def main():
                                   "kind": "oracle", "sample": sample.replace(", once", f", {reps} times") + f" ({cpu_s:.2f} s each; numpy fp64, BLAS threads={nthreads}, "
                                   "attention loops single-threaded)"}
         if s.E == 0:
-            result["parity_vs_oracle"] = {"max_abs": float(np.abs(diff).max()),
-                                          "rel_l2": float(np.linalg.norm(diff) / np.linalg.norm(ref["out"]))}
+            # the bound the GPU tests apply to a layer output (a chain of bf16 boundary tensors): per element
+            # max(2e-2, |ref| * 2^-6), i.e. the stated 2e-2 at unit scale and two bf16 ulps above it; rel-L2 5e-3
+            bound = np.maximum(2e-2, np.abs(ref["out"]) * 2.0 ** -6)
+            rel = float(np.linalg.norm(diff) / np.linalg.norm(ref["out"]))
+            result["parity_vs_oracle"] = {"max_abs": float(np.abs(diff).max()), "max_abs_ref_magnitude": float(np.abs(ref["out"]).max()),
+                                          "max_err_over_bound": float((np.abs(diff) / bound).max()), "rel_l2": rel,
+                                          "within_tolerance": bool((np.abs(diff) <= bound).all() and rel <= 5e-3)}
     print(json.dumps(result))
 
 
