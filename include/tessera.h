@@ -266,7 +266,7 @@ int ts_layer_forward(const ts_layer_desc* desc, const ts_layer_weights* w, const
  * recorded and, on the copy stream, the boundary tensor is packed into the
  * micro-batch's contiguous staging slot and copied to pinned host memory (the
  * stand-in for the `send` on a cut edge).  Compute streams never wait for the
- * copy stream except before a workspace half is reused by a later micro-batch.
+ * copy stream except before a workspace slot is reused by a later micro-batch.
  *
  * ts_pipeline owns only HIP events.  boundary_mask bit i selects boundary i.
  * Layout: ts_pipeline_boundary_layout gives, for the flagged boundaries in
@@ -294,7 +294,7 @@ int ts_layer_forward(const ts_layer_desc* desc, const ts_layer_weights* w, const
  * time): a quarter of the events.  A boundary then leaves up to half a layer after it was produced, which
  * costs a consumer on another GPU latency, not throughput.
  * The call returns after enqueueing; steps may be enqueued back to back (each waits for the transfers of
- * the previous one that still read its workspace half); the caller synchronises the streams before it
+ * the previous one that still read its workspace slot); the caller synchronises the streams before it
  * reads the slots or frees the buffers.
  */
 #define TS_PIPE_COPY_SIDE_STREAM 0
@@ -313,7 +313,7 @@ size_t ts_pipeline_slot_stride(const ts_layer_desc* desc, int T, int B, uint64_t
  * rows its tokens append to the cache into slot i of dev_slots and host_slots (device memory and
  * device-addressable pinned host memory, slot stride ts_pipeline_kv_delta_stride(desc, Tmax), layout
  * [T][K row of nkv*d | V row of nkv*d] bf16, keys already rotated) with a small kernel on delta_stream,
- * which the compute streams wait for only before the workspace half is reused.  All streams here have
+ * which the compute streams wait for only before the workspace slot is reused.  All streams here have
  * the default priority.  Passing dev_slots = host_slots = NULL switches it off.  `bytes` is the size of
  * each of the two buffers; ts_pipeline_step checks it against n_mb * stride. */
 size_t ts_pipeline_kv_delta_stride(const ts_layer_desc* desc, int T);

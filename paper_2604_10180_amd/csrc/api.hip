@@ -635,9 +635,9 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
     if (mb[i].T > Tmax) Tmax = mb[i].T;
     if (mb[i].B > Bmax) Bmax = mb[i].B;
   }
-  const size_t half = round_up(plan_layer(d, Tmax, Bmax).total, 256);
-  TS_REQUIRE(ws != nullptr && ws_bytes >= 2 * half, TS_ERR_WORKSPACE, "ts_pipeline_step: workspace %zu bytes < required %zu",
-             ws_bytes, 2 * half);
+  const size_t slot_bytes = round_up(plan_layer(d, Tmax, Bmax).total, 256);
+  TS_REQUIRE(ws != nullptr && ws_bytes >= 2 * slot_bytes, TS_ERR_WORKSPACE,
+             "ts_pipeline_step: workspace %zu bytes < required %zu", ws_bytes, 2 * slot_bytes);
   const size_t stride = ts_pipeline_slot_stride(&d, Tmax, Bmax, boundary_mask);
   TS_REQUIRE(boundary_mask == 0 || (dev_staging && pinned_host && staging_bytes >= stride * (size_t)n_mb),
              TS_ERR_WORKSPACE, "ts_pipeline_step: staging %zu bytes < required %zu", staging_bytes, stride * (size_t)n_mb);
@@ -653,11 +653,11 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
   // with a slot of its own a micro-batch never waits for the transfers of an earlier one of the same step
   // (with two slots every micro-batch from the third on starts only after the last send of the one two before
   // it, which cannot begin before that one's last kernel).
-  const int nslot = (int)std::min<size_t>((size_t)n_mb, std::max<size_t>(2, ws_bytes / half));
-  const bool same_geometry = p->prev_nslot == nslot && p->prev_slot_bytes == half;
+  const int nslot = (int)std::min<size_t>((size_t)n_mb, std::max<size_t>(2, ws_bytes / slot_bytes));
+  const bool same_geometry = p->prev_nslot == nslot && p->prev_slot_bytes == slot_bytes;
   for (int i = 0; i < n_mb; ++i) {
     hipStream_t s = cs[i & 1];
-    char* wsh = reinterpret_cast<char*>(ws) + (size_t)(i % nslot) * half;
+    char* wsh = reinterpret_cast<char*>(ws) + (size_t)(i % nslot) * slot_bytes;
     // a slot is reused by every nslot-th micro-batch: wait until its boundary tensors have been packed before
     // overwriting them
     if (i >= nslot && boundary_mask != 0 && copy_mode != TS_PIPE_COPY_SERIALISED)
@@ -746,7 +746,7 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
         }
       }
       // coalesced sends leave after RoPE, after the second norm, after SwiGLU and at the end of the layer (the
-      // last one is then only the layer output: the next user of this workspace half waits for it)
+      // last one is then only the layer output: the next user of this workspace slot waits for it)
       // (TS_PIPE_COPY_COALESCED_HALVES: after the attention half of the layer and at the end)
       if (coalesce && (send_point(index) || pending.n == 4)) return flush(index);
       return TS_OK;
@@ -763,7 +763,7 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
     p->prev_kv_sent[h] = (last >= 0 && p->delta_on) ? last : -1;
   }
   p->prev_nslot = nslot;
-  p->prev_slot_bytes = half;
+  p->prev_slot_bytes = slot_bytes;
   return TS_OK;
 }
 

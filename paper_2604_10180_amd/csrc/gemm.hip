@@ -31,13 +31,14 @@ struct SkinnyArgs {
   long w_group_stride;      // elements between experts
 };
 
-// Workgroup: 4 waves; wave w owns 16*NT rows of W; the activation k-slab [MT*16, 128] is
-// staged in LDS and shared by the 4 waves.  K advances 128 per iteration; lane (r, g) of a
-// wave (r = lane%16, g = lane/16) holds for MFMA step j the 8 k-values of 16-byte chunk
-// j*4+g, so a row's four lanes read 64 contiguous bytes per load.
+// Workgroup: WAVES waves (4, 7 or 8); wave w owns 16*NT rows of W; the activation k-slab [MT*16, 128] is
+// staged in LDS and shared by all waves (the first four stage it).  K advances 128 per iteration; for MFMA
+// step j lane (r, g) of a wave (r = lane%16, g = lane/16) holds the 8 k-values of 16-byte chunk j*4+g of W row
+// r and of the token row it multiplies.  From 33 token rows on the W fragments are loaded straight from
+// global in that layout (a row's four lanes read 64 contiguous bytes per load); up to 32 rows W is fetched as
+// whole cache lines and rearranged through a per-wave LDS stage (see WSTAGE below).
 // WAVES = 7 exists because the number of workgroups should be a multiple of the 256 CUs (a CU's bandwidth is
-// capped, so 448 workgroups take as long as 512 would): 28672 output columns are 256 x 112.  The first four
-// waves stage the activation slab; all waves share it.
+// capped, so 448 workgroups take as long as 512 would): 28672 output columns are 256 x 112.
 template <int MT, int NT, bool GROUPED, int NS, int WAVES = 4>
 __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(SkinnyArgs a) {
   constexpr int ROWS = MT * 16;
