@@ -682,8 +682,7 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
     const bool halves = copy_mode == TS_PIPE_COPY_COALESCED_HALVES;
     const bool coalesce = copy_mode == TS_PIPE_COPY_COALESCED || halves;
     const bool serial = copy_mode == TS_PIPE_COPY_SERIALISED;
-    // send what is pending: one event on the compute stream, one pack launch on the copy stream
-    // a send point: on coalesced sends the designated boundaries and the end of the layer
+    // where coalesced sends leave: the designated boundaries and the end of the layer
     auto send_point = [&](int index) {
       if (halves) return index == TS_B_X2 || index == nb - 1;
       return index == TS_B_QKV || index == TS_B_H2 || index == TS_B_ACT || index == nb - 1;
@@ -697,6 +696,8 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
       armed = !serial && (coalesce ? send_point(index) && (flagged || pending.n > 0) : flagged);
       if (armed) arm_stop_event(p->boundary_ev[(size_t)i * TS_NB_MOE + index]);
     };
+    // send what is pending: the boundary's event (carried by its kernel, else recorded here), one pack launch
+    // on the copy stream
     auto flush = [&](int index) -> int {
       if (pending.n == 0) return TS_OK;
       hipEvent_t e = p->boundary_ev[(size_t)i * TS_NB_MOE + index];
@@ -712,8 +713,8 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
       armed = false;
       if (index == TS_B_QKV && p->delta_on) {
         // the K and V rows this step appends to the cache are columns [nq d, (nq + 2 nkv) d) of the projection
-        // buffer: one strided pack on the delta stream
-        // (the boundary's own event if the RoPE kernel carries it)
+        // buffer: one strided pack on the delta stream, behind the boundary's own event if the RoPE kernel
+        // carries it, else behind an event recorded here
         hipEvent_t ready = attached ? p->boundary_ev[(size_t)i * TS_NB_MOE + index] : p->kv_ready_ev[i];
         if (!attached) TS_HIP(hipEventRecord(ready, s));
         TS_HIP(hipStreamWaitEvent(p->delta_stream, ready, 0));
