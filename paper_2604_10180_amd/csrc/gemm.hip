@@ -512,19 +512,18 @@ SkinnyPlan plan_skinny(int M, int N, int K) {
       if (p.S > 16) p.S = 16;
     }
   }
-  // Up to 64 token rows: also consider seven- and eight-wave workgroups (112 / 128 weight rows).  The model
-  // behind the choice: the most loaded CU runs ceil(workgroups / 256) of them, a workgroup's traffic is its
-  // weight slice plus the activation rows it re-reads from L2 (about a third as expensive per byte), and
-  // every K slice adds partial-sum traffic.  Measured with it: 8B shapes at 64 rows, gate/up 58 -> 49 us,
-  // down 34 -> 31 us, qkv 20 -> 18.6 us; 70B shapes at 32 rows, qkv 46 -> 36 us, o 40 -> 31 us (8B decode
-  // layer 0.2415 -> 0.2283 ms, 70B layer 0.763 -> 0.748 ms, same box); at 8 rows qkv 42 -> 34 us, o 39 -> 29 us.
-  if (M <= 64 && p.NT == 1) {   // (very wide outputs already stream at the cap with 128-row workgroups)
-    const int rows = M <= 16 ? 16 : (M <= 32 ? 32 : 64);
+  // Up to 64 token rows: also consider seven- and eight-wave workgroups (112 / 128 weight rows) and, from 33
+  // rows on, every form the kernel has.
+  if (M <= 32 && p.NT == 1) {   // (very wide outputs already stream at the cap with 128-row workgroups)
+    // The most loaded CU runs ceil(workgroups / 256) of them, a workgroup's traffic is its weight slice plus
+    // the activation rows it re-reads from L2 (about a third as expensive per byte), every K slice adds
+    // partial-sum traffic, and at equal width the wide forms measured a tenth faster.  Measured with it: 70B
+    // shapes at 32 rows, qkv 46 -> 36 us, o 40 -> 31 us; at 8 rows qkv 42 -> 34 us, o 39 -> 29 us.
+    const int rows = M <= 16 ? 16 : 32;
     auto score = [&](int waves, int NT, int S) {
       const int cols = 16 * waves * NT;
       const long wgs = (long)cdiv(N, cols) * S;
       const double quant = (double)((wgs + 255) / 256 * 256) / (double)wgs;
-      // (at equal width the seven/eight-wave form measured about a tenth faster: more loads in flight per slab)
       return quant * (1.0 + 0.35 * rows / cols) * (1.0 + 0.02 * S) * (waves > 4 ? 0.9 : 1.0);
     };
     const double legacy = score(4, p.NT, p.S);
@@ -541,6 +540,41 @@ SkinnyPlan plan_skinny(int M, int N, int K) {
           p.S = S;
         }
       }
+  } else if (M <= 64 && p.NT == 1) {
+    // 33 to 64 rows: every form (4, 7 or 8 waves x 16 or 32 weight rows per wave x 1..16 K slices) is scored in
+    // bytes through the most loaded CU: workgroups on that CU x (the workgroup's weight slice + its activation
+    // rows at half the cost per byte + 40 KB for filling and draining its ring) + the fp32 partials of a K
+    // split, written and read back, at 1.5 x the cost per byte.  The constants are a fit to a sweep of all
+    // forms over the projection shapes of the 8B and 70B layers; at 64 rows the choice is the best form measured
+    // for all four 8B shapes (qkv 24.5 -> 22.9 us and o 20.9 -> 18.3 us including their reduce kernels, by
+    // using four K slices instead of five and eight; 8B decode layer 0.2245 -> 0.2204 ms).  Up to 32 rows
+    // the same fit is 2 % faster kernel by kernel and 1 % slower on the pipelined step, where two projections
+    // share the chip and its fewer, fatter workgroups pack worse; the rule above stays there.
+    auto score = [&](int waves, int NT, int S) {
+      const int cols = 16 * waves * NT;
+      const int kslice = (int)round_up((size_t)cdiv(K, S), 128);
+      const int slices = cdiv(K, kslice);
+      const long wgs = (long)cdiv(N, cols) * slices;
+      double t = (double)((wgs + 255) / 256) * ((double)kslice * 2.0 * (cols + 0.5 * 64) + 40e3);
+      if (slices > 1) t += 2.0 * M * (double)N * 4.0 * slices / 256.0 * 1.5;
+      return t;
+    };
+    const double legacy = score(4, p.NT, p.S);
+    double best = legacy;
+    int maxs = K / 512;
+    maxs = maxs < 1 ? 1 : (maxs > 16 ? 16 : maxs);
+    for (int waves : {4, 7, 8})
+      for (int NT : {1, 2})
+        for (int S = 1; S <= maxs && N >= 16 * waves * NT; ++S) {
+          if ((long)cdiv(N, 16 * waves * NT) * S < 128) continue;   // at least half the CUs
+          const double sc = score(waves, NT, S);
+          if (sc < 0.97 * legacy && sc < best) {
+            best = sc;
+            p.waves = waves;
+            p.NT = NT;
+            p.S = S;
+          }
+        }
   }
   p.kslice = (int)round_up((size_t)cdiv(K, p.S), 128);
   p.S = cdiv(K, p.kslice);
