@@ -139,9 +139,12 @@ __device__ __forceinline__ void gemm_mfma256_body(const ts_bf16* __restrict__ A,
   // agree).  16 rows x 128 bytes = 2048 bytes per fragment; the swizzle depends on the row only through r16.
   const int r16 = lane & 15, kq = lane >> 4;
   const int f = (r16 & 7) ^ (r16 >> 3);
+  // lane groups kq and kq + 2 (lanes l and l + 32) are served together by the LDS: their chunks must differ in the
+  // lowest bit, or the swizzle sends the two to the same banks (measured: half of all LDS cycles in conflict)
+  const int kperm = ((kq & 1) << 1) | (kq >> 1);
   int frag_off[2];
 #pragma unroll
-  for (int sl = 0; sl < 2; ++sl) frag_off[sl] = r16 * 128 + (((sl * 4 + kq) ^ f) * 16);
+  for (int sl = 0; sl < 2; ++sl) frag_off[sl] = r16 * 128 + (((sl * 4 + kperm) ^ f) * 16);
   const int wbase = wn * 128 * 128;
   const int abase = 32768 + wm * 64 * 128;
 
