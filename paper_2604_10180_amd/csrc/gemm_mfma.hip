@@ -18,7 +18,7 @@
 //
 // What bounds it (8192 x 28672 x 4096): power.  With all-zero operands (full clock) the kernel runs at
 // 1.69 PFLOP/s: 2.0 without its ring loads, 1.79 when every load hits L2, and the L2 warm-up below closes most
-// of the gap to that (1.47 without it).  With random operands every structural variant lands at 1.20-1.24
+// of the gap to that (1.47 without it).  With random operands every structural variant lands at 1.2-1.3
 // (1.81 without the ring loads, 1.34 with L2 hits only): the matrix cores, the fragment reads, the L2->LDS
 // stream and the L2 misses each take their share of a fixed power budget, and the clock drops to 1.8 GHz.
 // The vendor library (same 256 x 256 x 64 tile, same MFMA shape) reaches 1.39-1.43 there and 2.14 on zeros.
