@@ -22,10 +22,14 @@
  *     memory.  The caller owns every buffer and keeps it alive (and does not
  *     overwrite inputs) until the enqueued work has finished.
  *   - Accumulation is fp32; results are rounded once (nearest-even) to bf16.
- *   - Return value: TS_OK or a negative TS_ERR_* code.  On error nothing has
- *     been enqueued.  Argument checks run before the first HIP call, so they
- *     work on a host without a GPU.  ts_last_error() gives a thread-local
- *     detail string for the last failing call on this thread.
+ *   - Return value: TS_OK or a negative TS_ERR_* code.  Argument, shape and
+ *     workspace checks run before the first HIP call (so they work on a host
+ *     without a GPU), and a call they reject has enqueued nothing.  A
+ *     TS_ERR_HIP raised by the runtime in the middle of a call that launches
+ *     several kernels (ts_layer_forward, ts_pipeline_step, the split-K and
+ *     split-KV paths) leaves the earlier launches enqueued; output and
+ *     workspace contents are then undefined.  ts_last_error() gives a
+ *     thread-local detail string for the last failing call on this thread.
  *   - Output buffers must not alias inputs except where a parameter is
  *     documented as in/out.
  */
@@ -268,7 +272,8 @@ int ts_layer_forward(const ts_layer_desc* desc, const ts_layer_weights* w, const
  * stand-in for the `send` on a cut edge).  Compute streams never wait for the
  * copy stream except before a workspace slot is reused by a later micro-batch.
  *
- * ts_pipeline owns only HIP events.  boundary_mask bit i selects boundary i.
+ * ts_pipeline owns only HIP events (created by the first step, so creating and
+ * destroying a pipeline needs no GPU).  boundary_mask bit i selects boundary i.
  * Layout: ts_pipeline_boundary_layout gives, for the flagged boundaries in
  * kernel order, byte offsets inside one micro-batch slot (offsets[n] = slot
  * bytes).  Slot i of dev_staging / pinned_host starts at i * slot_stride where
@@ -276,11 +281,14 @@ int ts_layer_forward(const ts_layer_desc* desc, const ts_layer_weights* w, const
  * dev_staging: device, >= n_mb*slot_stride bytes.  pinned_host: HOST pinned
  * memory of the same size that the device can address (hipHostMalloc, or a
  * torch tensor created with pin_memory): the pack kernel stores to it
- * directly, no copy-engine command is issued.  ws: device, >= 2 * ts_layer_workspace_bytes(Tmax,Bmax)
- * rounded up to 256 each, where Tmax/Bmax are the largest over micro-batches.  The step uses as many
+ * directly, no copy-engine command is issued.  ws: device, at least two workspace slots of
+ * ts_pipeline_workspace_slot_bytes(desc, Ts, Bs, n_mb) bytes each: the largest, over the micro-batches, of
+ * ts_layer_workspace_bytes(desc, T_i, B_i) rounded up to 256 (that size is NOT monotone in T or B, so the
+ * plan of the largest micro-batch is not enough; TS_ERR_WORKSPACE otherwise).  The step uses as many
  * workspace slots of that size as ws_bytes holds (at most n_mb): micro-batch i works in slot i % nslot and
- * waits, before it starts, for the transfers of the micro-batch that used the slot before it.  With n_mb
- * slots no micro-batch waits for a transfer of its own step.
+ * waits, before it starts, for the transfers and the kernels of the micro-batch that used the slot before
+ * it, in this step or the previous one, whichever streams those ran on.  With n_mb slots no micro-batch
+ * waits for a transfer of its own step.
  * All micro-batches must flag the same boundaries; their T may differ (the
  * layout is computed for each T; slot_stride uses the largest).
  * copy_mode: TS_PIPE_COPY_SIDE_STREAM sends every flagged boundary as soon as its kernel is enqueued (one
@@ -307,6 +315,9 @@ void ts_pipeline_destroy(ts_pipeline* p);
 int ts_pipeline_boundary_layout(const ts_layer_desc* desc, int T, int B, uint64_t boundary_mask,
                                 size_t* offsets /* host, [n+1] */, int* n_boundaries);
 size_t ts_pipeline_slot_stride(const ts_layer_desc* desc, int T, int B, uint64_t boundary_mask);
+/* Bytes of one workspace slot of ts_pipeline_step for micro-batches of Ts[i] tokens / Bs[i] sequences (HOST
+ * arrays of n_mb entries); 0 on invalid arguments.  Host-only arithmetic. */
+size_t ts_pipeline_workspace_slot_bytes(const ts_layer_desc* desc, const int32_t* Ts, const int32_t* Bs, int n_mb);
 /* Background replication of the KV-cache delta (Sec. 4: buffers with a cross-iteration dependency keep a
  * replica per GPU and the rows written in an iteration are propagated asynchronously, apart from the
  * dependency transfers).  Once set, every ts_pipeline_step also packs, for each micro-batch i, the K and V

@@ -227,8 +227,13 @@ BOUNDARY_ORDER_MOE = ("h1", "qkv", "attn", "x2", "h2", "logits", "gate_up", "act
 
 
 def layer_forward(shape, weights: dict, io: dict, mode: str, round_boundaries: bool = False,
-                  forced_route=None) -> dict:
+                  forced_route=None, perturb=None) -> dict:
     """Full decoder layer; returns every kernel-boundary tensor plus 'out'.
+
+    perturb: optional {boundary name: callable(array) -> array}, applied to that kernel's result before it is
+    stored (and, with round_boundaries, before it is rounded).  The default (None) changes nothing.  Tests use
+    it to measure how a kernel-sized disturbance of one buffer travels through the bf16 roundings of the
+    buffers after it, which is what an end-to-end comparison of two bf16 pipelines sees.
 
     shape: object with H, nq, nkv, d, F, E, k, eps, rope_base.
     weights: gamma1, w_qkv, w_o, gamma2, w_gate_up, w_down (+ w_router for MoE), float arrays.
@@ -237,12 +242,18 @@ def layer_forward(shape, weights: dict, io: dict, mode: str, round_boundaries: b
     forced_route: optional (idx, w) to teacher-force the routing decision.
     """
     s = shape
-    R = round_bf16 if round_boundaries else (lambda a: a)
+    rnd = round_bf16 if round_boundaries else (lambda a: a)
+    perturb = perturb or {}
     x = np.asarray(io["x"], F64)
     T = x.shape[0]
     scale = 1.0 / np.sqrt(s.d)
     r = {}
-    r["h1"] = R(rmsnorm(x, weights["gamma1"], s.eps))
+    def R(a, name=None):
+        if name in perturb:
+            a = perturb[name](a)
+        return rnd(a)
+
+    r["h1"] = R(rmsnorm(x, weights["gamma1"], s.eps), "h1")
     qkv = gemm(r["h1"], weights["w_qkv"])
     if round_boundaries:
         qkv = R(qkv)                      # the projection's own output buffer
@@ -258,13 +269,13 @@ def layer_forward(shape, weights: dict, io: dict, mode: str, round_boundaries: b
         attn = attention_decode(q, io["kcache"], io["vcache"], io["seq_lens"], scale)
     else:
         attn = attention_prefill(q, kk, vv, io["cu_seqlens"], scale, causal=True)
-    r["attn"] = R(attn.reshape(T, nqd))
-    r["x2"] = R(gemm(r["attn"], weights["w_o"], residual=x))
-    r["h2"] = R(rmsnorm(r["x2"], weights["gamma2"], s.eps))
+    r["attn"] = R(attn.reshape(T, nqd), "attn")
+    r["x2"] = R(gemm(r["attn"], weights["w_o"], residual=x), "x2")
+    r["h2"] = R(rmsnorm(r["x2"], weights["gamma2"], s.eps), "h2")
     if s.E == 0:
-        r["gate_up"] = R(gemm(r["h2"], weights["w_gate_up"]))
-        r["act"] = R(swiglu(r["gate_up"]))
-        r["out"] = R(gemm(r["act"], weights["w_down"], residual=r["x2"]))
+        r["gate_up"] = R(gemm(r["h2"], weights["w_gate_up"]), "gate_up")
+        r["act"] = R(swiglu(r["gate_up"]), "act")
+        r["out"] = R(gemm(r["act"], weights["w_down"], residual=r["x2"]), "out")
     else:
         logits = gemm(r["h2"], weights["w_router"])
         r["logits"] = logits.astype(np.float32).astype(F64) if round_boundaries else logits
@@ -275,10 +286,10 @@ def layer_forward(shape, weights: dict, io: dict, mode: str, round_boundaries: b
             _, _, counts, offsets, perm = _regroup(idx, s.E)
         r["topk_idx"], r["topk_w"], r["counts"], r["offsets"], r["perm"] = idx, w, counts, offsets, perm
         row_map = perm // s.k
-        r["gate_up"] = R(moe_gemm(r["h2"], row_map, weights["w_gate_up"], offsets))
-        r["act"] = R(swiglu(r["gate_up"]))
-        r["y"] = R(moe_gemm(r["act"], None, weights["w_down"], offsets))
-        r["out"] = R(moe_combine(r["y"], perm, w, r["x2"], T, s.k))
+        r["gate_up"] = R(moe_gemm(r["h2"], row_map, weights["w_gate_up"], offsets), "gate_up")
+        r["act"] = R(swiglu(r["gate_up"]), "act")
+        r["y"] = R(moe_gemm(r["act"], None, weights["w_down"], offsets), "y")
+        r["out"] = R(moe_combine(r["y"], perm, w, r["x2"], T, s.k), "out")
     return r
 
 

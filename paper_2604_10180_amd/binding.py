@@ -26,6 +26,7 @@ EXPORTS = [
     "ts_attention_decode", "ts_attention_prefill", "ts_swiglu", "ts_moe_route", "ts_moe_gemm", "ts_moe_combine",
     "ts_layer_workspace_bytes", "ts_layer_boundary", "ts_layer_moe_buffers", "ts_layer_forward",
     "ts_pipeline_create", "ts_pipeline_destroy", "ts_pipeline_boundary_layout", "ts_pipeline_slot_stride",
+    "ts_pipeline_workspace_slot_bytes",
     "ts_pipeline_step", "ts_pipeline_kv_delta_stride", "ts_pipeline_set_kv_delta", "ts_pipeline_set_link_slowdown", "ts_ddg_build", "ts_layer_ddg", "ts_layer_node_name", "ts_layer_cut_mask", "ts_plan_policy", "ts_plan_lower_bound",
     "ts_monitor_create", "ts_monitor_destroy", "ts_monitor_record", "ts_monitor_advance",
 ]
@@ -85,7 +86,7 @@ def _load() -> C.CDLL:
     for n in ("ts_strerror", "ts_last_error", "ts_version"):
         getattr(lib, n).restype = C.c_char_p
     for n in ("ts_gemm_workspace_bytes", "ts_attention_decode_workspace_bytes", "ts_layer_workspace_bytes",
-              "ts_pipeline_slot_stride", "ts_pipeline_kv_delta_stride"):
+              "ts_pipeline_slot_stride", "ts_pipeline_kv_delta_stride", "ts_pipeline_workspace_slot_bytes"):
         getattr(lib, n).restype = C.c_size_t
     lib.ts_pipeline_destroy.restype = None
     lib.ts_layer_node_name.restype = C.c_char_p
@@ -121,6 +122,7 @@ lib.ts_pipeline_destroy.argtypes = [_p]
 lib.ts_pipeline_boundary_layout.argtypes = [C.POINTER(LayerDesc), _i, _i, _u64, C.POINTER(_z), C.POINTER(_i)]
 lib.ts_pipeline_slot_stride.argtypes = [C.POINTER(LayerDesc), _i, _i, _u64]
 lib.ts_pipeline_kv_delta_stride.argtypes = [C.POINTER(LayerDesc), _i]
+lib.ts_pipeline_workspace_slot_bytes.argtypes = [C.POINTER(LayerDesc), C.POINTER(C.c_int32), C.POINTER(C.c_int32), _i]
 lib.ts_pipeline_set_kv_delta.argtypes = [_p, _p, _p, _p, _z]
 lib.ts_pipeline_set_link_slowdown.argtypes = [_p, C.c_int]
 lib.ts_pipeline_step.argtypes = [_p, C.POINTER(LayerWeights), C.POINTER(LayerIO), _i, C.POINTER(_p), _p, _u64, _i,
@@ -299,6 +301,11 @@ def ts_pipeline_boundary_layout(desc: LayerDesc, T: int, B: int, mask: int):
 
 def ts_pipeline_slot_stride(desc: LayerDesc, T: int, B: int, mask: int) -> int:
     return lib.ts_pipeline_slot_stride(C.byref(desc), T, B, mask & (2 ** 64 - 1))
+
+
+def ts_pipeline_workspace_slot_bytes(desc: LayerDesc, Ts: Sequence[int], Bs: Sequence[int]) -> int:
+    n = len(Ts)
+    return lib.ts_pipeline_workspace_slot_bytes(C.byref(desc), (C.c_int32 * n)(*Ts), (C.c_int32 * n)(*Bs), n)
 
 
 def ts_pipeline_kv_delta_stride(desc: LayerDesc, T: int) -> int:

@@ -506,23 +506,49 @@ int ts_layer_forward(const ts_layer_desc* desc, const ts_layer_weights* w, const
 struct ts_pipeline {
   ts_layer_desc desc;
   int max_mb;
+  bool events_ready = false;            // events are created by the first step (creation itself needs no GPU)
   std::vector<hipEvent_t> boundary_ev;  // [max_mb][TS_NB_MOE]
   std::vector<hipEvent_t> packed_ev;    // [max_mb]
   std::vector<hipEvent_t> kv_ready_ev;  // [max_mb] compute stream: K/V rows of the step are in the projection buffer
   std::vector<hipEvent_t> kv_sent_ev;   // [max_mb] delta stream: rows have left
+  // [2][max_mb] compute stream: the micro-batch's last kernel has been enqueued.  Two sets used by alternate
+  // steps, so that a step can wait for the previous step's events after it has recorded some of its own.
+  std::vector<hipEvent_t> done_ev;
+  int parity = 0;
   // background replication of the rows appended to the KV cache (off while delta_stream is null)
   hipStream_t delta_stream = nullptr;
   char* delta_dev = nullptr;
   char* delta_host = nullptr;
   size_t delta_bytes = 0;
   bool delta_on = false;
-  // what the previous step left in flight on the side streams, per workspace slot (-1: nothing), and the slot
-  // geometry it used (a step with another geometry waits for all of it)
-  std::vector<int> prev_packed, prev_kv_sent;   // [max_mb]
+  // what the previous step left in flight, per workspace slot (-1: nothing): the last micro-batch whose boundary
+  // sends / KV rows / kernels used the slot, the compute stream it ran on, and the slot geometry of that step
+  // (a step with another geometry waits for all of it)
+  std::vector<int> prev_packed, prev_kv_sent, prev_done;   // [max_mb]
+  std::vector<hipStream_t> prev_stream;                    // [max_mb]
   size_t prev_slot_bytes = 0;
   int prev_nslot = 0;
+  const void* prev_ws = nullptr;
   int link_slowdown = 1;   // every boundary tensor crosses the host link this many times
 };
+
+static int pipeline_ensure_events(ts_pipeline* p) {
+  if (p->events_ready) return TS_OK;
+  const int m = p->max_mb;
+  const int nbe = m * TS_NB_MOE;
+  const int n = nbe + 5 * m;
+  for (int i = 0; i < n; ++i) {
+    hipEvent_t e;
+    TS_HIP(hipEventCreateWithFlags(&e, hipEventDisableTiming | hipEventReleaseToDevice));
+    if (i < nbe) p->boundary_ev.push_back(e);
+    else if (i < nbe + m) p->packed_ev.push_back(e);
+    else if (i < nbe + 2 * m) p->kv_ready_ev.push_back(e);
+    else if (i < nbe + 3 * m) p->kv_sent_ev.push_back(e);
+    else p->done_ev.push_back(e);
+  }
+  p->events_ready = true;
+  return TS_OK;
+}
 
 int ts_pipeline_create(const ts_layer_desc* desc, int max_micro_batches, ts_pipeline** out) {
   int rc = validate_desc(desc, "ts_pipeline_create");
@@ -535,20 +561,8 @@ int ts_pipeline_create(const ts_layer_desc* desc, int max_micro_batches, ts_pipe
   p->max_mb = max_micro_batches;
   p->prev_packed.assign(max_micro_batches, -1);
   p->prev_kv_sent.assign(max_micro_batches, -1);
-  const int nbe = max_micro_batches * TS_NB_MOE;
-  const int n = nbe + 3 * max_micro_batches;
-  for (int i = 0; i < n; ++i) {
-    hipEvent_t e;
-    hipError_t err = hipEventCreateWithFlags(&e, hipEventDisableTiming | hipEventReleaseToDevice);
-    if (err != hipSuccess) {
-      ts_pipeline_destroy(p);
-      return check_hip(err, "hipEventCreateWithFlags");
-    }
-    if (i < nbe) p->boundary_ev.push_back(e);
-    else if (i < nbe + max_micro_batches) p->packed_ev.push_back(e);
-    else if (i < nbe + 2 * max_micro_batches) p->kv_ready_ev.push_back(e);
-    else p->kv_sent_ev.push_back(e);
-  }
+  p->prev_done.assign(max_micro_batches, -1);
+  p->prev_stream.assign(max_micro_batches, nullptr);
   *out = p;
   return TS_OK;
 }
@@ -559,7 +573,19 @@ void ts_pipeline_destroy(ts_pipeline* p) {
   for (hipEvent_t e : p->packed_ev) (void)hipEventDestroy(e);
   for (hipEvent_t e : p->kv_ready_ev) (void)hipEventDestroy(e);
   for (hipEvent_t e : p->kv_sent_ev) (void)hipEventDestroy(e);
+  for (hipEvent_t e : p->done_ev) (void)hipEventDestroy(e);
   delete p;
+}
+
+size_t ts_pipeline_workspace_slot_bytes(const ts_layer_desc* desc, const int32_t* Ts, const int32_t* Bs, int n_mb) {
+  if (desc == nullptr || Ts == nullptr || Bs == nullptr || n_mb <= 0) return 0;
+  if (validate_desc(desc, "ts_pipeline_workspace_slot_bytes") != TS_OK) return 0;
+  size_t slot = 0;
+  for (int i = 0; i < n_mb; ++i) {
+    if (Ts[i] < 0 || Bs[i] < 0) return 0;
+    slot = std::max(slot, round_up(plan_layer(*desc, Ts[i], Bs[i]).total, 256));
+  }
+  return slot;
 }
 
 size_t ts_pipeline_kv_delta_stride(const ts_layer_desc* desc, int T) {
@@ -635,9 +661,14 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
     if (mb[i].T > Tmax) Tmax = mb[i].T;
     if (mb[i].B > Bmax) Bmax = mb[i].B;
   }
-  const size_t slot_bytes = round_up(plan_layer(d, Tmax, Bmax).total, 256);
+  // A micro-batch lays its workspace slot out with the plan of its own (T, B), and that size is not monotone in
+  // T or B (the split-K and split-KV plans change form with the row count), so the slot is the largest plan
+  // over the micro-batches, not the plan of the largest micro-batch.
+  size_t slot_bytes = 0;
+  for (int i = 0; i < n_mb; ++i) slot_bytes = std::max(slot_bytes, round_up(plan_layer(d, mb[i].T, mb[i].B).total, 256));
   TS_REQUIRE(ws != nullptr && ws_bytes >= 2 * slot_bytes, TS_ERR_WORKSPACE,
-             "ts_pipeline_step: workspace %zu bytes < required %zu", ws_bytes, 2 * slot_bytes);
+             "ts_pipeline_step: workspace %zu bytes < required %zu (two slots of ts_pipeline_workspace_slot_bytes)",
+             ws_bytes, 2 * slot_bytes);
   const size_t stride = ts_pipeline_slot_stride(&d, Tmax, Bmax, boundary_mask);
   TS_REQUIRE(boundary_mask == 0 || (dev_staging && pinned_host && staging_bytes >= stride * (size_t)n_mb),
              TS_ERR_WORKSPACE, "ts_pipeline_step: staging %zu bytes < required %zu", staging_bytes, stride * (size_t)n_mb);
@@ -648,27 +679,48 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
   const size_t dstride = ts_pipeline_kv_delta_stride(&d, Tmax);
   TS_REQUIRE(!p->delta_on || p->delta_bytes >= dstride * (size_t)n_mb, TS_ERR_WORKSPACE,
              "ts_pipeline_step: KV delta slots %zu bytes < required %zu", p->delta_bytes, dstride * (size_t)n_mb);
+  {
+    int rc = pipeline_ensure_events(p);
+    if (rc != TS_OK) return rc;
+  }
 
   // Micro-batch i works in workspace slot i % nslot, with as many slots as the workspace holds (two at least):
   // with a slot of its own a micro-batch never waits for the transfers of an earlier one of the same step
   // (with two slots every micro-batch from the third on starts only after the last send of the one two before
   // it, which cannot begin before that one's last kernel).
   const int nslot = (int)std::min<size_t>((size_t)n_mb, std::max<size_t>(2, ws_bytes / slot_bytes));
-  const bool same_geometry = p->prev_nslot == nslot && p->prev_slot_bytes == slot_bytes;
+  const bool same_geometry = p->prev_nslot == nslot && p->prev_slot_bytes == slot_bytes && p->prev_ws == ws;
+  const bool sends = boundary_mask != 0 && copy_mode != TS_PIPE_COPY_SERIALISED;
+  hipEvent_t* done_now = p->done_ev.data() + (size_t)p->parity * p->max_mb;
+  hipEvent_t* done_prev = p->done_ev.data() + (size_t)(p->parity ^ 1) * p->max_mb;
+  // Steps may follow each other without a host synchronisation.  What the previous step left in flight in slot h:
+  // the sends that read it, and the kernels of its last user when those ran on another stream.
+  auto wait_prev_slot = [&](hipStream_t s, int h) -> int {
+    if (p->prev_packed[h] >= 0) TS_HIP(hipStreamWaitEvent(s, p->packed_ev[p->prev_packed[h]], 0));
+    if (p->prev_kv_sent[h] >= 0) TS_HIP(hipStreamWaitEvent(s, p->kv_sent_ev[p->prev_kv_sent[h]], 0));
+    if (p->prev_done[h] >= 0 && p->prev_stream[h] != s) TS_HIP(hipStreamWaitEvent(s, done_prev[p->prev_done[h]], 0));
+    return TS_OK;
+  };
+  if (!same_geometry) {   // other slots than last time: both streams wait for all of it, before this step records anything
+    for (int c = 0; c < (n_mb > 1 ? 2 : 1); ++c)
+      for (int h = 0; h < p->prev_nslot; ++h) {
+        int rc = wait_prev_slot(cs[c], h);
+        if (rc != TS_OK) return rc;
+      }
+  }
   for (int i = 0; i < n_mb; ++i) {
     hipStream_t s = cs[i & 1];
     char* wsh = reinterpret_cast<char*>(ws) + (size_t)(i % nslot) * slot_bytes;
-    // a slot is reused by every nslot-th micro-batch: wait until its boundary tensors have been packed before
-    // overwriting them
-    if (i >= nslot && boundary_mask != 0 && copy_mode != TS_PIPE_COPY_SERIALISED)
-      TS_HIP(hipStreamWaitEvent(s, p->packed_ev[i - nslot], 0));
-    if (i >= nslot && p->delta_on) TS_HIP(hipStreamWaitEvent(s, p->kv_sent_ev[i - nslot], 0));   // its rows sit in that slot
-    if (i < nslot) {   // steps may follow each other without a host synchronisation: the previous step's last users
-      for (int h = 0; h < p->prev_nslot; ++h) {
-        if (same_geometry && h != i) continue;   // same slots as last time: only this slot's last user matters
-        if (p->prev_packed[h] >= 0) TS_HIP(hipStreamWaitEvent(s, p->packed_ev[p->prev_packed[h]], 0));
-        if (p->prev_kv_sent[h] >= 0) TS_HIP(hipStreamWaitEvent(s, p->kv_sent_ev[p->prev_kv_sent[h]], 0));
-      }
+    // A slot is reused by every nslot-th micro-batch.  Its next user waits (a) until the side streams have read
+    // what they send from it and (b), when it runs on the other compute stream (odd nslot), until the previous
+    // user's kernels are done: the sends cover only the kernels up to the last flagged boundary.
+    if (i >= nslot) {
+      if (sends) TS_HIP(hipStreamWaitEvent(s, p->packed_ev[i - nslot], 0));
+      if (p->delta_on) TS_HIP(hipStreamWaitEvent(s, p->kv_sent_ev[i - nslot], 0));   // its rows sit in that slot
+      if (cs[(i - nslot) & 1] != s) TS_HIP(hipStreamWaitEvent(s, done_now[i - nslot], 0));
+    } else if (same_geometry && i < p->prev_nslot) {   // same slots as last time: only this slot's last user matters
+      int rc = wait_prev_slot(s, i);
+      if (rc != TS_OK) return rc;
     }
     const LayerPlan plan = plan_layer(d, mb[i].T, mb[i].B);
     size_t offs[TS_NB_MOE + 1];
@@ -755,16 +807,24 @@ int ts_pipeline_step(ts_pipeline* p, const ts_layer_weights* w, const ts_layer_i
     rc = layer_forward_impl(d, *w, mb[i], wsh, s, pre, hook);
     disarm_stop_event();
     if (rc != TS_OK) return rc;
-    if (boundary_mask != 0 && copy_mode != TS_PIPE_COPY_SERIALISED) TS_HIP(hipEventRecord(p->packed_ev[i], copy));
+    if (sends) TS_HIP(hipEventRecord(p->packed_ev[i], copy));
+    // the slot's next user may run on the other compute stream (in this step when nslot is odd; in the next
+    // step whenever the caller passes other streams or another workspace): mark the end of this one's kernels
+    const bool last_user = i + nslot >= n_mb;
+    if (last_user || cs[(i + nslot) & 1] != s) TS_HIP(hipEventRecord(done_now[i], s));
   }
   for (int h = 0; h < nslot; ++h) {
     int last = -1;   // last micro-batch that used slot h
     for (int i = h; i < n_mb; i += nslot) last = i;
-    p->prev_packed[h] = (last >= 0 && boundary_mask != 0 && copy_mode != TS_PIPE_COPY_SERIALISED) ? last : -1;
+    p->prev_packed[h] = (last >= 0 && sends) ? last : -1;
     p->prev_kv_sent[h] = (last >= 0 && p->delta_on) ? last : -1;
+    p->prev_done[h] = last;
+    p->prev_stream[h] = last >= 0 ? cs[last & 1] : nullptr;
   }
   p->prev_nslot = nslot;
   p->prev_slot_bytes = slot_bytes;
+  p->prev_ws = ws;
+  p->parity ^= 1;
   return TS_OK;
 }
 

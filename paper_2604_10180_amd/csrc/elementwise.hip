@@ -8,8 +8,8 @@ namespace ts {
 // ---------------------------------------------------------------- RMSNorm
 // One workgroup per row; the row stays in registers between the reduction and the scaling.
 template <int VPT>
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* __restrict__ x, const uint4* __restrict__ gamma,
-                                                      uint4* __restrict__ y, int H8, float eps, float inv_h,
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* x, const uint4* __restrict__ gamma,
+                                                      uint4* y, int H8, float eps, float inv_h,
                                                       int32_t* __restrict__ zero, int nzero) {
   const int row = blockIdx.x;
   const int tid = threadIdx.x;

@@ -28,14 +28,18 @@ def to_np(t: torch.Tensor) -> np.ndarray:
     return t.detach().float().cpu().numpy().astype(np.float64)
 
 
-def errors(got: np.ndarray, ref: np.ndarray, chain: bool = False):
+def errors(got: np.ndarray, ref: np.ndarray, chain: bool = False, ulps: int = 0):
+    """(max-abs in units where the per-element bound is MAX_ABS, relative L2).  `ulps` = how many bf16 ulps of
+    |ref| an element may be off (default 1, with chain=True 2; a product of two chained bf16 values, the SwiGLU
+    output compared end to end, takes 3: one ulp from either factor and its own rounding)."""
     got = np.asarray(got, np.float64).reshape(-1)
     ref = np.asarray(ref, np.float64).reshape(-1)
     assert got.shape == ref.shape, (got.shape, ref.shape)
     if ref.size == 0:
         return 0.0, 0.0
     assert np.all(np.isfinite(got)), "non-finite values in GPU output"
-    scale = np.maximum(1.0, np.abs(ref) * (2.0 ** (-6 if chain else -7)) / MAX_ABS)
+    n_ulps = ulps if ulps > 0 else (2 if chain else 1)
+    scale = np.maximum(1.0, np.abs(ref) * n_ulps * (2.0 ** -7) / MAX_ABS)
     max_abs = float(np.max(np.abs(got - ref) / scale))
     den = float(np.linalg.norm(ref))
     rel = float(np.linalg.norm(got - ref) / den) if den > 0 else float(np.linalg.norm(got - ref))

@@ -106,3 +106,46 @@ def test_layer_planning_host_only(B):
     assert B.ts_layer_workspace_bytes(bad, 4, 4) == 0
     with pytest.raises(B.TesseraError):
         B.ts_layer_boundary(bad, 4, 4, 0)
+
+
+def test_pipeline_workspace_slot_is_the_largest_plan_not_the_plan_of_the_largest_micro_batch(B):
+    """The layer's workspace size is not monotone in the row count (split-K and split-KV plans change form), and
+    every micro-batch lays its slot out with its own plan: the slot must hold the largest of them.  All of it is
+    checked before the first HIP call, so it runs on a host without a GPU (the fake pointers are never used)."""
+    from workloads import CONFIGS
+    for name in ("8b_decode", "70b_pipeline"):
+        s = CONFIGS[name].shape
+        desc = B.make_desc(s, Lcap=4096, mode="decode")
+        sizes = {T: B.ts_layer_workspace_bytes(desc, T, T) for T in range(1, 130)}
+        inversions = [T for T in range(1, 129) if sizes[T] > sizes[T + 1]]
+        for T in range(1, 129):
+            slot = B.ts_pipeline_workspace_slot_bytes(desc, [T + 1, T], [T + 1, T])
+            assert slot % 256 == 0 and slot >= sizes[T] and slot >= sizes[T + 1]
+            assert slot == max((sizes[T] + 255) // 256 * 256, (sizes[T + 1] + 255) // 256 * 256)
+        if not inversions:
+            continue
+        T = inversions[0]           # plan(T) > plan(T + 1)
+        pipe = B.ts_pipeline_create(desc, 2)
+        try:
+            fake = 4096
+            wts = B.LayerWeights(*([fake] * 8), 0)
+            mbs = [B.LayerIO(fake, fake, fake, fake, fake, None, fake, fake, t, t, 0) for t in (T + 1, T)]
+
+            class Buf:   # stands in for a device buffer of a given size at a fake address
+                def __init__(self, n):
+                    self.n = n
+                def data_ptr(self):
+                    return fake
+                def numel(self):
+                    return self.n
+                def element_size(self):
+                    return 1
+            too_small = 2 * ((sizes[T + 1] + 255) // 256 * 256)      # two slots sized for the larger micro-batch only
+            assert too_small < 2 * B.ts_pipeline_workspace_slot_bytes(desc, [T + 1, T], [T + 1, T])
+            with pytest.raises(B.TesseraError) as e:
+                B.ts_pipeline_step(pipe, wts, mbs, [0, 0], 0, 0, None, None, Buf(too_small))
+            assert e.value.code == B.TS_ERR_WORKSPACE
+        finally:
+            B.ts_pipeline_destroy(pipe)
+    assert inversions or name != "70b_pipeline"
+    assert B.ts_pipeline_workspace_slot_bytes(desc, [], []) == 0

@@ -4,21 +4,22 @@
 Where the oracle cannot evaluate everything in seconds it evaluates whole sequences that it
 can (prefill: first and last sequence; 70B decode: every sequence, kv heads widened once).
 
-How a whole layer is checked.  Every kernel boundary is a bf16 buffer, so a layer carries
-about eight successive roundings; against the exact (never rounded) oracle that alone gives
-a relative L2 error of 4-5e-3 and a 5-sigma element error of several 1e-2 at these widths,
-whatever the kernels do, and rounding the oracle's own boundaries does not help (a value
-that differs by 1e-6 upstream rounds the other way and comes back as a whole ulp).  So:
-  * stage by stage, teacher-forced: each kernel's output is compared with the oracle's
-    kernel applied to the GPU's own input buffers (downloaded bf16 values).  This isolates
-    each kernel at full size, in situ, and the stated bounds apply as they stand:
-    max-abs 2e-2 and rel-L2 5e-3 (see parity.py for large magnitudes and for `chain`);
-  * end to end against the exact oracle on the original inputs: the layer's outputs (x2, out)
-    measure rel-L2 4.6e-3 .. 5.1e-3 on the five configurations, i.e. they sit AT the stated
-    5e-3, and that figure is the accumulated storage rounding (each stage adds its own
-    1.66e-3 in quadrature, the SwiGLU product doubles the incoming error), not a kernel
-    property.  The end-to-end gate is therefore rel-L2 <= 6e-3 and max-abs <= 0.25; interior
-    buffers are reported and held to rel-L2 <= 1e-2.
+How a whole layer is checked.  Every kernel boundary is a bf16 buffer, so a layer carries about eight
+successive roundings.
+  * stage by stage, teacher-forced: each kernel's output is compared with the oracle's kernel applied to the
+    GPU's own input buffers (downloaded bf16 values).  This isolates each kernel at full size, in situ, and the
+    stated bounds apply as they stand: max-abs 2e-2 and rel-L2 5e-3 (see parity.py for large magnitudes and for
+    `chain`);
+  * end to end against the oracle that rounds its own boundary buffers to bf16 (check_rounded): rel-L2 <= 5e-3
+    at every boundary as stated (measured 3.3e-3 .. 4.2e-3 at the layer output); the largest element error is
+    gated at the stated 2e-2 or, where the rounding oracle itself moves by more under a disturbance of its
+    attention output of the size bf16 probabilities cause, at twice that movement (measured with the oracle in
+    the same test).  Rounding the oracle's boundaries does not make the roundings common-mode: a sub-ulp
+    difference tips a share of them, and each later boundary re-quantises the result
+    (tests/test_oracle_rounding_sensitivity.py);
+  * end to end against the exact (never rounded) oracle: reported, with a loose regression gate (rel-L2 <= 6e-3
+    for x2/out, 1e-2 for interior buffers, max-abs <= 0.25): the layer outputs measure rel-L2 4.6e-3 .. 5.1e-3
+    there, the accumulated storage rounding of eight bf16 boundaries.
 """
 import math
 
@@ -102,6 +103,47 @@ def check_end_to_end(got_fn, ref_exact, names, tag):
     return worst
 
 
+ROUNDED_MAX_ABS = 2e-2     # the stated bounds, as they stand (parity.py: per element max(2e-2, two bf16 ulps of |ref|))
+ROUNDED_REL_L2 = 5e-3
+ATTN_NOISE = 2e-3          # relative size of what bf16 attention probabilities add to the attention output
+
+
+def attn_noise(seed=0):
+    rng = np.random.default_rng(seed)
+    return {"attn": lambda a: a * (1.0 + ATTN_NOISE * rng.standard_normal(a.shape))}
+
+
+def check_rounded(got_fn, ref_rounded, names, tag, ref_disturbed=None):
+    """End to end against the oracle that rounds every kernel-boundary buffer to bf16 where the GPU path stores
+    one.  The storage roundings are then on both sides, but they are not common-mode: whatever the kernels add
+    below one ulp (fp32 against fp64 accumulation, bf16 attention probabilities: 2e-3 of the attention output)
+    tips a share of the roundings the other way, and every later boundary re-quantises the difference
+    (tests/test_oracle_rounding_sensitivity.py measures this with the oracle alone).
+    Gate, every boundary: relative L2 <= 5e-3 as stated; largest element error <= 2e-2 in parity.py's units (per
+    element max(2e-2, two bf16 ulps of |ref|; three for the SwiGLU output), or, where the oracle itself moves by
+    more than that under an attention-sized disturbance (`ref_disturbed`: the same oracle with its attention
+    output disturbed by 2e-3 before rounding), at most twice what the oracle moves.  Raw max-abs is printed."""
+    rep, bad = {}, []
+    for n in names:
+        g, r = got_fn(n).reshape(-1), np.asarray(ref_rounded[n], np.float64).reshape(-1)
+        ulps = 3 if n == "act" else 2
+        ma, rl = errors(g, r, ulps=ulps)
+        raw = float(np.abs(g - r).max()) if g.size else 0.0
+        rep[n] = {"rel_l2": round(rl, 6), "max_abs": round(ma, 5), "max_abs_raw": round(raw, 5),
+                  "differing": round(float(np.mean(g != r)), 4)}
+        lim = ROUNDED_MAX_ABS
+        if ref_disturbed is not None:
+            d = np.asarray(ref_disturbed[n], np.float64).reshape(-1)
+            own_ma, own_rl = errors(d, r, ulps=ulps)
+            rep[n].update({"oracle_own_max_abs": round(own_ma, 5), "oracle_own_rel_l2": round(own_rl, 6)})
+            lim = max(lim, 2.0 * own_ma)
+        if not (rl <= ROUNDED_REL_L2 and ma <= lim):
+            bad.append(n)
+    print(f"{tag} vs boundary-rounded oracle: {rep}", flush=True)
+    assert not bad, f"{tag} vs boundary-rounded oracle, over the gate at {bad}: {rep}"
+    return rep
+
+
 def check_stagewise(shape, mode, got_fn, w, x, pos, attn_ref_fn, tag, moe=None):
     """Teacher-forced per-kernel parity.  got_fn(name) -> GPU boundary (float64 view of the bf16
     buffer); attn_ref_fn(q, k, v) -> oracle attention output for the GPU's rotated q/k/v."""
@@ -152,6 +194,9 @@ def test_8b_decode_full(B):
     w64 = f64(weights, keep32=())
     exact = O.layer_forward(s, w64, f64(io), "decode")
     print("8b_decode end-to-end vs exact oracle:", check_end_to_end(L.boundary, exact, O.BOUNDARY_ORDER_DENSE, "8b_decode"))
+    rounded = O.layer_forward(s, w64, f64(io), "decode", round_boundaries=True)
+    disturbed = O.layer_forward(s, w64, f64(io), "decode", round_boundaries=True, perturb=attn_noise())
+    check_rounded(L.boundary, rounded, O.BOUNDARY_ORDER_DENSE, "8b_decode", disturbed)
     kc, vc = WL.as_f32(io["kcache"]), WL.as_f32(io["vcache"])
     def attn_ref(q, k, v):
         O.kv_append(kc, vc, k, v, np.arange(wl.B), np.full(wl.B, wl.ctx))
@@ -184,6 +229,11 @@ def test_8b_prefill_full_first_and_last_sequence(B):
         exact = O.layer_forward(s, w64, io_e, "prefill")
         got = lambda nm: L.boundary(nm, rows)
         print(f"8b_prefill seq {b} end-to-end vs exact:", check_end_to_end(got, exact, O.BOUNDARY_ORDER_DENSE, f"8b_prefill seq{b}"))
+        io_r = dict(io_e, kcache=np.zeros((1, s.nkv, n, s.d)), vcache=np.zeros((1, s.nkv, n, s.d)))
+        rounded = O.layer_forward(s, w64, io_r, "prefill", round_boundaries=True)
+        io_r = dict(io_e, kcache=np.zeros((1, s.nkv, n, s.d)), vcache=np.zeros((1, s.nkv, n, s.d)))
+        disturbed = O.layer_forward(s, w64, io_r, "prefill", round_boundaries=True, perturb=attn_noise())
+        check_rounded(got, rounded, O.BOUNDARY_ORDER_DENSE, f"8b_prefill seq{b}", disturbed)
         attn_ref = lambda q, k, v: O.attention_prefill(q, k, v, np.array([0, n]), 1 / math.sqrt(s.d), True)
         print(f"8b_prefill seq {b} stage-wise:", check_stagewise(s, "prefill", got, w64, io_e["x"], np.arange(n), attn_ref,
                                                                  f"8b_prefill seq{b}"))
@@ -214,6 +264,10 @@ def test_moe_decode_full_teacher_forced(B):
     forced = O.layer_forward(s, w64, f64(io), "decode", forced_route=(idx, wts))
     print("moe_decode end-to-end vs exact (expert half, routing teacher-forced):",
           check_end_to_end(L.boundary, forced, ("gate_up", "act", "y", "out"), "moe"))
+    rounded = O.layer_forward(s, w64, f64(io), "decode", round_boundaries=True, forced_route=(idx, wts))
+    disturbed = O.layer_forward(s, w64, f64(io), "decode", round_boundaries=True, forced_route=(idx, wts), perturb=attn_noise())
+    check_rounded(L.boundary, rounded, ("h1", "qkv", "attn", "x2", "h2", "gate_up", "act", "y", "out"),
+                  "moe_decode (routing teacher-forced)", disturbed)
     kc, vc = WL.as_f32(io["kcache"]), WL.as_f32(io["vcache"])
     def attn_ref(q, k, v):
         O.kv_append(kc, vc, k, v, np.arange(wl.B), np.full(wl.B, wl.ctx))
@@ -240,7 +294,7 @@ def test_70b_pipeline_full(B):
     layout = B.ts_pipeline_boundary_layout(desc, per, per, mask)
     staging = torch.zeros(stride * wl.n_micro, dtype=torch.uint8, device=DEV)
     host = torch.zeros(stride * wl.n_micro, dtype=torch.uint8).pin_memory()
-    half = (B.ts_layer_workspace_bytes(desc, per, per) + 255) // 256 * 256
+    half = B.ts_pipeline_workspace_slot_bytes(desc, [per] * wl.n_micro, [per] * wl.n_micro)
     ws = torch.zeros(2 * half, dtype=torch.uint8, device=DEV)
     outs, mbs, keep = [], [], []
     for i in range(wl.n_micro):
@@ -289,19 +343,27 @@ def test_70b_pipeline_full(B):
             j = names.index(nm)
             return to_np(stream[layout[j] // 2:layout[j + 1] // 2]).reshape(per, -1)
         e2e = check_end_to_end(got, exact, names, f"70b mb{i}")
+        sub_r = dict(sub, kcache=kc32[sl].copy(), vcache=vc32[sl].copy())
+        rounded = O.layer_forward(s, w64, sub_r, "decode", round_boundaries=True)
+        sub_r = dict(sub, kcache=kc32[sl].copy(), vcache=vc32[sl].copy())
+        disturbed = O.layer_forward(s, w64, sub_r, "decode", round_boundaries=True, perturb=attn_noise(i))
+        rnd = check_rounded(got, rounded, names, f"70b mb{i}", disturbed)
         kc_i, vc_i = kc32[sl].copy(), vc32[sl].copy()
         def attn_ref(q, k, v):
             O.kv_append(kc_i, vc_i, k, v, np.arange(per), sub["pos"])
             return O.attention_decode(q, kc_i, vc_i, sub["seq_lens"], 1 / math.sqrt(s.d))
         st = check_stagewise(s, "decode", got, w64, sub["x"], sub["pos"], attn_ref, f"70b mb{i}")
-        print(f"70b micro-batch {i}: lens={lens[i * per:(i + 1) * per]}\n   end-to-end vs exact: {e2e}\n   stage-wise: {st}")
+        print(f"70b micro-batch {i}: lens={lens[i * per:(i + 1) * per]}\n   end-to-end vs exact: {e2e}\n"
+              f"   end-to-end vs boundary-rounded oracle: {rnd}\n   stage-wise: {st}")
 
 
 def test_70b_pipeline_boundary_copies_overlap(B):
     """Sec. 3.3: the transfers of the boundary tensors hide behind the computation of the other
-    micro-batches.  Timed three ways on the 70B-shaped configuration (4 micro-batches of 8
-    sequences): no copies, all eight boundaries copied on the side stream, all copied on the
-    compute streams.  Wide margins: this is a timing test."""
+    micro-batches.  Timed on the 70B-shaped configuration (4 micro-batches of 8 sequences): no copies, all eight
+    boundaries sent from the side stream (per boundary, and coalesced), all of them copied on the compute streams.
+    Gate: the coalesced side-stream step costs at most 6 % over the copy-free step and is strictly faster than the
+    serialised one (medians of three interleaved timings; one re-measurement if a gate is missed, this is a
+    timing test on a shared machine)."""
     import bench
     wl = WL.CONFIGS["70b_pipeline"]
     s = wl.shape
@@ -311,12 +373,16 @@ def test_70b_pipeline_boundary_copies_overlap(B):
     wd = {k: v.to(DEV) for k, v in weights.items()}
     iod = {k: v.to(DEV) for k, v in io.items()}
     dev_set = (wd, iod, None, B.make_weights(wd), None)
+
+    def gates(r):
+        return (r["coalesced_ms"] <= 1.06 * r["no_copies_ms"] and r["coalesced_ms"] < r["serialised_ms"]
+                and r["side_stream_ms"] <= 1.08 * r["no_copies_ms"] and r["side_stream_ms"] < r["serialised_ms"])
     r = bench.time_pipeline(B, torch, wl, desc, dev_set, io, DEV, steps=10, warmup=3)
     print("70b pipeline step:", r)
-    assert r["side_stream_ms"] <= 1.15 * r["no_copies_ms"], r
-    assert r["side_stream_ms"] <= 1.03 * r["serialised_ms"], r
-    assert r["coalesced_ms"] <= 1.08 * r["no_copies_ms"], r
-    assert r["coalesced_ms"] <= 1.03 * r["serialised_ms"], r
+    if not gates(r):
+        r2 = bench.time_pipeline(B, torch, wl, desc, dev_set, io, DEV, steps=20, warmup=5, link_sweep=False)
+        print("70b pipeline step, re-measured:", r2)
+        assert gates(r2), (r, r2)
     # Sec. 5, interconnect sensitivity: with only the attention kernel's two edges cut, a link sixteen times
     # slower (about the 25 Gbps of the paper's sweep) still hides behind the other micro-batches; with every
     # boundary crossing it the step becomes link-bound
