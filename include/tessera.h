@@ -257,6 +257,35 @@ int ts_layer_boundary(const ts_layer_desc* desc, int T, int B, int index, size_t
 /* Where the MoE routing outputs live inside the workspace (host-only arithmetic):
  * offsets of logits f32[T,E], topk_idx i32[T,k], topk_w f32[T,k], counts i32[E], offsets i32[E+1], perm i32[T*k]. */
 int ts_layer_moe_buffers(const ts_layer_desc* desc, int T, int B, size_t ws_offsets[6]);
+/* The byte ranges that node `node` of the layer (the group of kernels that ends at kernel boundary `node`, see
+ * ts_layer_node_name) reads and writes when ts_layer_forward runs it: the hand-declared counterpart of the
+ * [min, max] range the paper's kernel analyzer derives per memory instruction (Sec. 3.1, "Memory access
+ * analysis"), and what ts_layer_ddg feeds to the dependency analysis.  An access names one of the layer's five
+ * buffers and a byte range inside it: offset, extent (the hull) and the bytes really touched inside the hull;
+ * iter_advance as in ts_access.  kind: TS_ACC_READ, TS_ACC_WRITE, or TS_ACC_PRIVATE for scratch that the node
+ * writes and reads back itself (split-K and split-KV partials, arrival counters, the inverse permutation of the
+ * MoE combine): it carries nothing between nodes and its contents are undefined afterwards.  Decode: kv_len =
+ * keys each sequence attends, the appended one included (the declaration assumes equal lengths; the append is
+ * one row per sequence and kv head at position kv_len - 1).  Prefill ignores kv_len.  Weights are never written
+ * and are left out.  HOST-only arithmetic; `out` is a host array of max_accesses entries; if more are needed,
+ * *n_accesses is the number and TS_ERR_WORKSPACE is returned with nothing written.
+ * A GPU test fills everything outside the declared write ranges with a pattern and everything the layer does
+ * not produce itself with NaNs and checks that the kernels stay inside these declarations. */
+#define TS_BUF_WORKSPACE 0
+#define TS_BUF_X 1
+#define TS_BUF_OUT 2
+#define TS_BUF_KCACHE 3
+#define TS_BUF_VCACHE 4
+#define TS_ACC_READ 0
+#define TS_ACC_WRITE 1
+#define TS_ACC_PRIVATE 2
+typedef struct ts_layer_access {
+  int32_t buffer, kind;
+  uint64_t offset, extent, bytes;
+  int64_t iter_advance;
+} ts_layer_access;
+int ts_layer_node_accesses(const ts_layer_desc* desc, int T, int B, int kv_len, int node, ts_layer_access* out,
+                           int max_accesses, int* n_accesses);
 /* Enqueues the whole layer on `stream` and returns; kernels only: no allocation, no memset, no copy-engine
  * command, no host synchronisation, so the call may be recorded into a HIP graph by stream capture and
  * replayed (sizes, pointers and sequence lengths are those of the capture; the lengths are read from

@@ -24,7 +24,7 @@ EXPORTS = [
     "ts_strerror", "ts_last_error", "ts_version", "ts_profile_begin", "ts_profile_end", "ts_rmsnorm", "ts_gemm_workspace_bytes", "ts_gemm_bf16",
     "ts_gemm_bf16_f32out", "ts_rope", "ts_rope_table", "ts_attention_decode_workspace_bytes",
     "ts_attention_decode", "ts_attention_prefill", "ts_swiglu", "ts_moe_route", "ts_moe_gemm", "ts_moe_combine",
-    "ts_layer_workspace_bytes", "ts_layer_boundary", "ts_layer_moe_buffers", "ts_layer_forward",
+    "ts_layer_workspace_bytes", "ts_layer_boundary", "ts_layer_moe_buffers", "ts_layer_node_accesses", "ts_layer_forward",
     "ts_pipeline_create", "ts_pipeline_destroy", "ts_pipeline_boundary_layout", "ts_pipeline_slot_stride",
     "ts_pipeline_workspace_slot_bytes",
     "ts_pipeline_step", "ts_pipeline_kv_delta_stride", "ts_pipeline_set_kv_delta", "ts_pipeline_set_link_slowdown", "ts_ddg_build", "ts_layer_ddg", "ts_layer_node_name", "ts_layer_cut_mask", "ts_plan_policy", "ts_plan_lower_bound",
@@ -52,6 +52,15 @@ class LayerWeights(C.Structure):
 class LayerIO(C.Structure):
     _fields_ = [(n, C.c_void_p) for n in ("x", "out", "pos", "seq_id", "seq_lens", "cu_seqlens", "kcache", "vcache")] + \
                [("T", C.c_int32), ("B", C.c_int32), ("max_seqlen", C.c_int32)]
+
+
+class LayerAccess(C.Structure):
+    _fields_ = [("buffer", C.c_int32), ("kind", C.c_int32), ("offset", C.c_uint64), ("extent", C.c_uint64),
+                ("bytes", C.c_uint64), ("iter_advance", C.c_int64)]
+
+
+TS_BUF_WORKSPACE, TS_BUF_X, TS_BUF_OUT, TS_BUF_KCACHE, TS_BUF_VCACHE = range(5)
+TS_ACC_READ, TS_ACC_WRITE, TS_ACC_PRIVATE = range(3)
 
 
 class Access(C.Structure):
@@ -116,6 +125,7 @@ lib.ts_moe_combine.argtypes = [_p, _p, _p, _p, _p, _p, _i, _i, _i, _p]
 lib.ts_layer_workspace_bytes.argtypes = [C.POINTER(LayerDesc), _i, _i]
 lib.ts_layer_boundary.argtypes = [C.POINTER(LayerDesc), _i, _i, _i, C.POINTER(_z), C.POINTER(_z)]
 lib.ts_layer_moe_buffers.argtypes = [C.POINTER(LayerDesc), _i, _i, C.POINTER(_z)]
+lib.ts_layer_node_accesses.argtypes = [C.POINTER(LayerDesc), _i, _i, _i, _i, C.POINTER(LayerAccess), _i, C.POINTER(_i)]
 lib.ts_layer_forward.argtypes = [C.POINTER(LayerDesc), C.POINTER(LayerWeights), C.POINTER(LayerIO), _p, _z, _p]
 lib.ts_pipeline_create.argtypes = [C.POINTER(LayerDesc), _i, C.POINTER(_p)]
 lib.ts_pipeline_destroy.argtypes = [_p]
@@ -276,6 +286,17 @@ def ts_layer_moe_buffers(desc: LayerDesc, T: int, B: int):
     arr = (_z * 6)()
     _check(lib.ts_layer_moe_buffers(C.byref(desc), T, B, arr))
     return list(arr)
+
+
+def ts_layer_node_accesses(desc: LayerDesc, T: int, B: int, kv_len: int, node: int):
+    """[(buffer, kind, offset, extent, bytes, iter_advance)] declared for one node of the layer."""
+    n = _i()
+    rc = lib.ts_layer_node_accesses(C.byref(desc), T, B, kv_len, node, None, 0, C.byref(n))
+    if rc not in (TS_OK, TS_ERR_WORKSPACE):
+        _check(rc)
+    arr = (LayerAccess * max(1, n.value))()
+    _check(lib.ts_layer_node_accesses(C.byref(desc), T, B, kv_len, node, arr, n.value, C.byref(n)))
+    return [(a.buffer, a.kind, a.offset, a.extent, a.bytes, a.iter_advance) for a in arr[: n.value]]
 
 
 def ts_layer_forward(desc: LayerDesc, weights: LayerWeights, io: LayerIO, ws, stream=None) -> None:

@@ -488,6 +488,130 @@ int ts_layer_moe_buffers(const ts_layer_desc* desc, int T, int B, size_t ws_offs
   return TS_OK;
 }
 
+int ts_layer_node_accesses(const ts_layer_desc* desc, int T, int B, int kv_len, int node, ts_layer_access* out,
+                           int max_accesses, int* n_accesses) {
+  int rc = validate_desc(desc, "ts_layer_node_accesses");
+  if (rc != TS_OK) return rc;
+  const ts_layer_desc& d = *desc;
+  const bool moe = d.E > 0;
+  const int nb = moe ? TS_NB_MOE : TS_NB_DENSE;
+  TS_REQUIRE(T >= 1 && B >= 1 && node >= 0 && node < nb && n_accesses != nullptr && max_accesses >= 0 &&
+                 (out != nullptr || max_accesses == 0),
+             TS_ERR_INVALID_ARG, "ts_layer_node_accesses: bad arguments (T=%d B=%d node=%d)", T, B, node);
+  if (d.mode == TS_MODE_DECODE)
+    TS_REQUIRE(T == B && kv_len >= 1 && kv_len <= d.Lcap, TS_ERR_INVALID_ARG,
+               "ts_layer_node_accesses: decode needs T == B and 1 <= kv_len <= Lcap");
+  const LayerPlan p = plan_layer(d, T, B);
+  std::vector<ts_layer_access> acc;
+  auto add = [&](int buffer, int kind, uint64_t off, uint64_t extent, uint64_t bytes, int64_t adv = 0) {
+    if (extent == 0) return;
+    acc.push_back(ts_layer_access{buffer, kind, off, extent, bytes, adv});
+  };
+  auto full = [&](int buffer, int kind, uint64_t off, uint64_t n) { add(buffer, kind, off, n, n); };
+  // boundary i as the node that produces it writes it and as later nodes read it
+  auto bnd = [&](int kind, int i) {
+    if (i == nb - 1) full(TS_BUF_OUT, kind, 0, p.bytes[i]);
+    else full(TS_BUF_WORKSPACE, kind, boundary_offset(p, d, i), p.bytes[i]);
+  };
+  auto scratch = [&](size_t bytes) { full(TS_BUF_WORKSPACE, TS_ACC_PRIVATE, p.scratch, bytes); };
+  const uint64_t xbytes = (uint64_t)T * d.H * 2, row = (uint64_t)d.d * 2;
+  const uint64_t nqd = (uint64_t)d.nq * d.d, nqkv = (uint64_t)(d.nq + 2 * d.nkv) * d.d;
+  const uint64_t cache_bytes = (uint64_t)B * d.nkv * d.Lcap * row;
+  const int rows = moe ? T * d.k : T;
+  switch (node) {
+    case TS_B_H1:
+      full(TS_BUF_X, TS_ACC_READ, 0, xbytes);
+      bnd(TS_ACC_WRITE, TS_B_H1);
+      // the first kernel of the layer also zeroes the arrival counters of the attention kernel
+      full(TS_BUF_WORKSPACE, TS_ACC_PRIVATE, p.counters, (uint64_t)p.counter_words * 4);
+      break;
+    case TS_B_QKV:
+      bnd(TS_ACC_READ, TS_B_H1);
+      bnd(TS_ACC_WRITE, TS_B_QKV);
+      scratch(gemm_workspace_bytes(T, (int)nqkv, d.H));
+      if (d.mode == TS_MODE_DECODE) {   // one new row per (sequence, kv head), one position further every iteration
+        for (int b = 0; b < B; ++b)
+          for (int h = 0; h < d.nkv; ++h) {
+            const uint64_t o = (((uint64_t)b * d.nkv + h) * d.Lcap + (uint64_t)(kv_len - 1)) * row;
+            add(TS_BUF_KCACHE, TS_ACC_WRITE, o, row, row, (int64_t)row);
+            add(TS_BUF_VCACHE, TS_ACC_WRITE, o, row, row, (int64_t)row);
+          }
+      } else {
+        const uint64_t kv_new = std::min<uint64_t>((uint64_t)T * d.nkv * row, cache_bytes);
+        add(TS_BUF_KCACHE, TS_ACC_WRITE, 0, cache_bytes, kv_new);
+        add(TS_BUF_VCACHE, TS_ACC_WRITE, 0, cache_bytes, kv_new);
+      }
+      break;
+    case TS_B_ATTN:
+      if (d.mode == TS_MODE_DECODE) {
+        add(TS_BUF_WORKSPACE, TS_ACC_READ, p.qkv, p.bytes[TS_B_QKV], (uint64_t)T * nqd * 2);   // the q columns
+        const uint64_t kv_read = (uint64_t)B * d.nkv * kv_len * row;
+        add(TS_BUF_KCACHE, TS_ACC_READ, 0, cache_bytes, kv_read);
+        add(TS_BUF_VCACHE, TS_ACC_READ, 0, cache_bytes, kv_read);
+        scratch(attention_decode_workspace_bytes(B, d.nq, d.nkv, d.d, d.Lcap));
+        full(TS_BUF_WORKSPACE, TS_ACC_PRIVATE, p.counters, (uint64_t)p.counter_words * 4);
+      } else {
+        bnd(TS_ACC_READ, TS_B_QKV);
+      }
+      bnd(TS_ACC_WRITE, TS_B_ATTN);
+      break;
+    case TS_B_X2:
+      bnd(TS_ACC_READ, TS_B_ATTN);
+      full(TS_BUF_X, TS_ACC_READ, 0, xbytes);
+      bnd(TS_ACC_WRITE, TS_B_X2);
+      scratch(gemm_workspace_bytes(T, d.H, d.nq * d.d));
+      break;
+    case TS_B_H2:
+      bnd(TS_ACC_READ, TS_B_X2);
+      bnd(TS_ACC_WRITE, TS_B_H2);
+      break;
+    case TS_B_GATE_UP:
+      bnd(TS_ACC_READ, TS_B_H2);
+      bnd(TS_ACC_WRITE, TS_B_GATE_UP);
+      if (!moe) {
+        scratch(gemm_workspace_bytes(T, 2 * d.F, d.H));
+        if (gemm_mfma256_glu_supported(T, d.F, d.H)) bnd(TS_ACC_WRITE, TS_B_ACT);   // activation in the epilogue
+      } else {   // router, routing and the grouped projection: the routing tables are this node's side outputs
+        full(TS_BUF_WORKSPACE, TS_ACC_WRITE, p.logits, (uint64_t)T * d.E * 4);
+        full(TS_BUF_WORKSPACE, TS_ACC_WRITE, p.topk_idx, (uint64_t)T * d.k * 4);
+        full(TS_BUF_WORKSPACE, TS_ACC_WRITE, p.topk_w, (uint64_t)T * d.k * 4);
+        full(TS_BUF_WORKSPACE, TS_ACC_WRITE, p.counts, (uint64_t)d.E * 4);
+        full(TS_BUF_WORKSPACE, TS_ACC_WRITE, p.offsets, (uint64_t)(d.E + 1) * 4);
+        full(TS_BUF_WORKSPACE, TS_ACC_WRITE, p.perm, (uint64_t)T * d.k * 4);
+        if (!moe_router_supported(d.E, d.H)) scratch(gemm_workspace_bytes(T, d.E, d.H));
+      }
+      break;
+    case TS_B_ACT:
+      bnd(TS_ACC_READ, TS_B_GATE_UP);
+      bnd(TS_ACC_WRITE, TS_B_ACT);
+      break;
+    default:
+      if (!moe) {   // TS_B_OUT_DENSE
+        bnd(TS_ACC_READ, TS_B_ACT);
+        bnd(TS_ACC_READ, TS_B_X2);
+        bnd(TS_ACC_WRITE, TS_B_OUT_DENSE);
+        scratch(gemm_workspace_bytes(T, d.H, d.F));
+      } else if (node == TS_B_Y_MOE) {
+        bnd(TS_ACC_READ, TS_B_ACT);
+        full(TS_BUF_WORKSPACE, TS_ACC_READ, p.offsets, (uint64_t)(d.E + 1) * 4);
+        bnd(TS_ACC_WRITE, TS_B_Y_MOE);
+      } else {   // TS_B_OUT_MOE
+        bnd(TS_ACC_READ, TS_B_Y_MOE);
+        bnd(TS_ACC_READ, TS_B_X2);
+        full(TS_BUF_WORKSPACE, TS_ACC_READ, p.perm, (uint64_t)rows * 4);
+        full(TS_BUF_WORKSPACE, TS_ACC_READ, p.topk_w, (uint64_t)rows * 4);
+        full(TS_BUF_WORKSPACE, TS_ACC_PRIVATE, p.inv, (uint64_t)rows * 4);
+        bnd(TS_ACC_WRITE, TS_B_OUT_MOE);
+      }
+      break;
+  }
+  *n_accesses = (int)acc.size();
+  TS_REQUIRE((int)acc.size() <= max_accesses, TS_ERR_WORKSPACE, "ts_layer_node_accesses: %zu accesses, room for %d", acc.size(),
+             max_accesses);
+  std::copy(acc.begin(), acc.end(), out);
+  return TS_OK;
+}
+
 int ts_layer_forward(const ts_layer_desc* desc, const ts_layer_weights* w, const ts_layer_io* io, void* ws,
                      size_t ws_bytes, void* stream) {
   int rc = validate_desc(desc, "ts_layer_forward");

@@ -337,80 +337,47 @@ int build_layer_nodes(const ts_layer_desc& d, int T, int B, int kv_len, int n_la
   auto X = [&](int l) { return EXT + (uint64_t)l * per_layer; };                 // input of layer l = output of l-1
   auto KC = [&](int l) { return X(l) + up(xbytes); };
   auto VC = [&](int l) { return KC(l) + up(cache_bytes); };
-  uint64_t boff[TS_NB_MOE], bbytes[TS_NB_MOE];
-  for (int i = 0; i < nb; ++i) {
-    size_t o, n;
-    int rc = ts_layer_boundary(&d, T, B, i, &o, &n);
-    if (rc != TS_OK) return rc;
-    boff[i] = o == (size_t)-1 ? 0 : WS + o;
-    bbytes[i] = n;
-  }
   size_t moe_off[6] = {0, 0, 0, 0, 0, 0};
-  uint64_t moe_bytes[6] = {0, 0, 0, 0, 0, 0};
   if (moe) {
     int rc = ts_layer_moe_buffers(&d, T, B, moe_off);
     if (rc != TS_OK) return rc;
-    moe_bytes[0] = (uint64_t)T * d.E * 4; moe_bytes[1] = (uint64_t)T * d.k * 4; moe_bytes[2] = (uint64_t)T * d.k * 4;
-    moe_bytes[3] = (uint64_t)d.E * 4; moe_bytes[4] = (uint64_t)(d.E + 1) * 4; moe_bytes[5] = (uint64_t)T * d.k * 4;
   }
-  const uint64_t nqd = (uint64_t)d.nq * d.d, row = (uint64_t)d.d * 2;
+  // The declared accesses of every node (the same list a GPU test holds the kernels to), once per layer shape.
+  // Scratch private to a node carries nothing between nodes and is left out; the routing tables of a MoE layer
+  // are data that travels outside the kernel boundaries (`kSideTables`).
+  std::vector<std::vector<ts_layer_access>> decl(nb);
+  for (int i = 0; i < nb; ++i) {
+    int n = 0;
+    int rc = ts_layer_node_accesses(&d, T, B, d.mode == TS_MODE_DECODE ? kv_len : 1, i, nullptr, 0, &n);
+    if (rc != TS_OK && rc != TS_ERR_WORKSPACE) return rc;
+    decl[i].resize(n);
+    if (n > 0) {
+      rc = ts_layer_node_accesses(&d, T, B, d.mode == TS_MODE_DECODE ? kv_len : 1, i, decl[i].data(), n, &n);
+      if (rc != TS_OK) return rc;
+    }
+  }
   out.reads.assign((size_t)n_layers * nb, {});
   out.writes.assign((size_t)n_layers * nb, {});
   const bool bb = which & kBoundaryBuffers, st = which & kSideTables;
-  auto full = [](uint64_t a, uint64_t n) { return ts_access{a, n, n, 0}; };
   for (int l = 0; l < n_layers; ++l) {
-    auto R = [&](int node) -> std::vector<ts_access>& { return out.reads[(size_t)l * nb + node]; };
-    auto W = [&](int node) -> std::vector<ts_access>& { return out.writes[(size_t)l * nb + node]; };
-    auto bnd = [&](int i) { return full(i == nb - 1 ? X(l + 1) : boff[i], bbytes[i]); };
-    if (bb) {
-      R(TS_B_H1).push_back(full(X(l), xbytes));
-      W(TS_B_H1).push_back(bnd(TS_B_H1));
-      R(TS_B_QKV).push_back(bnd(TS_B_H1));
-      W(TS_B_QKV).push_back(bnd(TS_B_QKV));
-      if (d.mode == TS_MODE_DECODE) {
-        for (int b = 0; b < B; ++b)
-          for (int h = 0; h < d.nkv; ++h) {
-            const uint64_t o = (((uint64_t)b * d.nkv + h) * d.Lcap + (uint64_t)(kv_len - 1)) * row;
-            W(TS_B_QKV).push_back(ts_access{KC(l) + o, row, row, (int64_t)row});
-            W(TS_B_QKV).push_back(ts_access{VC(l) + o, row, row, (int64_t)row});
-          }
-        R(TS_B_ATTN).push_back(ts_access{boff[TS_B_QKV], bbytes[TS_B_QKV], (uint64_t)T * nqd * 2, 0});
-        const uint64_t kv_read = (uint64_t)B * d.nkv * kv_len * row;
-        R(TS_B_ATTN).push_back(ts_access{KC(l), cache_bytes, kv_read, 0});
-        R(TS_B_ATTN).push_back(ts_access{VC(l), cache_bytes, kv_read, 0});
-      } else {
-        const uint64_t kv_new = (uint64_t)T * d.nkv * row;
-        W(TS_B_QKV).push_back(ts_access{KC(l), cache_bytes, std::min(kv_new, cache_bytes), 0});
-        W(TS_B_QKV).push_back(ts_access{VC(l), cache_bytes, std::min(kv_new, cache_bytes), 0});
-        R(TS_B_ATTN).push_back(bnd(TS_B_QKV));
+    for (int i = 0; i < nb; ++i) {
+      for (const ts_layer_access& a : decl[i]) {
+        if (a.kind == TS_ACC_PRIVATE) continue;
+        bool side = false;
+        if (moe && a.buffer == TS_BUF_WORKSPACE)
+          for (size_t o : moe_off) side = side || a.offset == (uint64_t)o;
+        if (side ? !st : !bb) continue;
+        uint64_t base = 0;
+        switch (a.buffer) {
+          case TS_BUF_WORKSPACE: base = WS; break;
+          case TS_BUF_X: base = X(l); break;
+          case TS_BUF_OUT: base = X(l + 1); break;
+          case TS_BUF_KCACHE: base = KC(l); break;
+          default: base = VC(l); break;
+        }
+        const ts_access acc{base + a.offset, a.extent, a.bytes, a.iter_advance};
+        (a.kind == TS_ACC_WRITE ? out.writes : out.reads)[(size_t)l * nb + i].push_back(acc);
       }
-      W(TS_B_ATTN).push_back(bnd(TS_B_ATTN));
-      R(TS_B_X2).push_back(bnd(TS_B_ATTN));
-      R(TS_B_X2).push_back(full(X(l), xbytes));
-      W(TS_B_X2).push_back(bnd(TS_B_X2));
-      R(TS_B_H2).push_back(bnd(TS_B_X2));
-      W(TS_B_H2).push_back(bnd(TS_B_H2));
-      R(TS_B_GATE_UP).push_back(bnd(TS_B_H2));
-      W(TS_B_GATE_UP).push_back(bnd(TS_B_GATE_UP));
-      R(TS_B_ACT).push_back(bnd(TS_B_GATE_UP));
-      W(TS_B_ACT).push_back(bnd(TS_B_ACT));
-      if (!moe) {
-        R(TS_B_OUT_DENSE).push_back(bnd(TS_B_ACT));
-        R(TS_B_OUT_DENSE).push_back(bnd(TS_B_X2));
-        W(TS_B_OUT_DENSE).push_back(bnd(TS_B_OUT_DENSE));
-      } else {
-        R(TS_B_Y_MOE).push_back(bnd(TS_B_ACT));
-        W(TS_B_Y_MOE).push_back(bnd(TS_B_Y_MOE));
-        R(TS_B_OUT_MOE).push_back(bnd(TS_B_Y_MOE));
-        R(TS_B_OUT_MOE).push_back(bnd(TS_B_X2));
-        W(TS_B_OUT_MOE).push_back(bnd(TS_B_OUT_MOE));
-      }
-    }
-    if (st && moe) {
-      for (int i = 0; i < 6; ++i) W(TS_B_GATE_UP).push_back(full(WS + moe_off[i], moe_bytes[i]));
-      R(TS_B_Y_MOE).push_back(full(WS + moe_off[4], moe_bytes[4]));     // expert offsets
-      R(TS_B_OUT_MOE).push_back(full(WS + moe_off[5], moe_bytes[5]));   // permutation
-      R(TS_B_OUT_MOE).push_back(full(WS + moe_off[2], moe_bytes[2]));   // routing weights
     }
   }
   out.io.resize(out.reads.size());
