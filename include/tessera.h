@@ -145,6 +145,18 @@ int ts_attention_decode(const ts_bf16* q, const ts_bf16* kcache, const ts_bf16* 
                         const int32_t* seq_lens, ts_bf16* out, int B, int nq, int nkv, int d,
                         int Lcap, float scale, void* ws, size_t ws_bytes, void* stream);
 
+/* The same call for callers that cannot allocate or carry a workspace (code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc): the split-KV partials live in a device array that is part
+ * of the library image, ts_attention_decode_static_limit() bytes (16 MiB) on every GPU the library runs on, held
+ * until the process ends.  Same kernels and bit-identical results to ts_attention_decode.  Shapes whose
+ * partials (ts_attention_decode_workspace_bytes) exceed the limit are rejected with TS_ERR_WORKSPACE before
+ * anything is enqueued.  The call allocates and frees nothing.  All calls on one GPU share that GPU's array:
+ * calls that may run at the same time on one GPU (different streams) race and must be ordered by the caller. */
+size_t ts_attention_decode_static_limit(void);
+int ts_attention_decode_static(const ts_bf16* q, const ts_bf16* kcache, const ts_bf16* vcache,
+                               const int32_t* seq_lens, ts_bf16* out, int B, int nq, int nkv, int d,
+                               int Lcap, float scale, void* stream);
+
 /* ---------------------------------------------------------------------------
  * Prefill attention over packed fresh sequences: the compute-bound tiled
  * kernel (Sec. 2.3).  Token at in-sequence index i attends keys j <= i of its

@@ -23,7 +23,7 @@ TS_B_Y_MOE, TS_B_OUT_MOE, TS_NB_MOE = 7, 8, 9
 EXPORTS = [
     "ts_strerror", "ts_last_error", "ts_version", "ts_profile_begin", "ts_profile_end", "ts_rmsnorm", "ts_gemm_workspace_bytes", "ts_gemm_bf16",
     "ts_gemm_bf16_f32out", "ts_rope", "ts_rope_table", "ts_attention_decode_workspace_bytes",
-    "ts_attention_decode", "ts_attention_prefill", "ts_swiglu", "ts_moe_route", "ts_moe_gemm", "ts_moe_combine",
+    "ts_attention_decode", "ts_attention_decode_static", "ts_attention_decode_static_limit", "ts_attention_prefill", "ts_swiglu", "ts_moe_route", "ts_moe_gemm", "ts_moe_combine",
     "ts_layer_workspace_bytes", "ts_layer_boundary", "ts_layer_moe_buffers", "ts_layer_node_accesses", "ts_layer_forward",
     "ts_pipeline_create", "ts_pipeline_destroy", "ts_pipeline_boundary_layout", "ts_pipeline_slot_stride",
     "ts_pipeline_workspace_slot_bytes",
@@ -95,7 +95,8 @@ def _load() -> C.CDLL:
     for n in ("ts_strerror", "ts_last_error", "ts_version"):
         getattr(lib, n).restype = C.c_char_p
     for n in ("ts_gemm_workspace_bytes", "ts_attention_decode_workspace_bytes", "ts_layer_workspace_bytes",
-              "ts_pipeline_slot_stride", "ts_pipeline_kv_delta_stride", "ts_pipeline_workspace_slot_bytes"):
+              "ts_pipeline_slot_stride", "ts_pipeline_kv_delta_stride", "ts_pipeline_workspace_slot_bytes",
+              "ts_attention_decode_static_limit"):
         getattr(lib, n).restype = C.c_size_t
     lib.ts_pipeline_destroy.restype = None
     lib.ts_layer_node_name.restype = C.c_char_p
@@ -117,6 +118,8 @@ lib.ts_rope.argtypes = [_p, _p, _p, _i, _i, _p, _p, _p, _i, _p, _p, _i, _i, _i, 
 lib.ts_rope_table.argtypes = [_p, _i, _i, _f]
 lib.ts_attention_decode_workspace_bytes.argtypes = [_i, _i, _i, _i, _i]
 lib.ts_attention_decode.argtypes = [_p, _p, _p, _p, _p, _i, _i, _i, _i, _i, _f, _p, _z, _p]
+lib.ts_attention_decode_static.argtypes = [_p, _p, _p, _p, _p, _i, _i, _i, _i, _i, _f, _p]
+lib.ts_attention_decode_static_limit.argtypes = []
 lib.ts_attention_prefill.argtypes = [_p, _p, _p, _i, _i, _p, _p, _i, _i, _i, _i, _i, _i, _f, _i, _p]
 lib.ts_swiglu.argtypes = [_p, _p, _i, _i, _p]
 lib.ts_moe_route.argtypes = [_p, _i, _i, _i, _p, _p, _p, _p, _p, _p]
@@ -225,6 +228,16 @@ def ts_attention_decode(q, kcache, vcache, seq_lens, out, B: int, nq: int, nkv: 
                         ws=None, stream=None) -> None:
     _check(lib.ts_attention_decode(_ptr(q), _ptr(kcache), _ptr(vcache), _ptr(seq_lens), _ptr(out), B, nq, nkv, d, Lcap,
                                    scale, _ptr(ws), _nbytes(ws), _stream(stream)))
+
+
+def ts_attention_decode_static_limit() -> int:
+    return lib.ts_attention_decode_static_limit()
+
+
+def ts_attention_decode_static(q, kcache, vcache, seq_lens, out, B: int, nq: int, nkv: int, d: int, Lcap: int,
+                               scale: float, stream=None) -> None:
+    _check(lib.ts_attention_decode_static(_ptr(q), _ptr(kcache), _ptr(vcache), _ptr(seq_lens), _ptr(out), B, nq, nkv, d,
+                                          Lcap, scale, _stream(stream)))
 
 
 def ts_attention_prefill(q, k, v, q_stride: int, kv_stride: int, cu_seqlens, out, S: int, T: int, max_seqlen: int,

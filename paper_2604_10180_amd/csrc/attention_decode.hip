@@ -12,6 +12,7 @@
 //
 // Split-KV: grid (chunk, kv head, sequence); each workgroup reduces its chunk to an
 // un-normalised (m, l, O) triple per head in fp32; a second kernel merges the chunks.
+#include <mutex>
 #include "common.hpp"
 
 namespace ts {
@@ -361,4 +362,63 @@ int launch_attention_decode(const ts_bf16* q, int q_stride, const ts_bf16* kc, c
   return TS_OK;
 }
 
+// ---- the entry point that allocates nothing: split-KV partials in a file-scope device array ---------------
+// Each GPU the library runs on holds its own copy of the array, at its own address, until the process ends.
+// In host code the array's name is only a stand-in for the symbol: the device address is looked up once per
+// device (with that device current) and kept; everything on the host uses the looked-up pointer.
+constexpr size_t kStaticScratchBytes = (size_t)16 << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void** out) {
+  int dev = -1;
+  TS_HIP(hipGetDevice(&dev));
+  TS_REQUIRE(dev >= 0 && dev < kMaxDevices, TS_ERR_UNSUPPORTED_SHAPE, "ts_attention_decode_static: device index %d", dev);
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (g_scratch_ptr[dev] == nullptr) {
+    void* found = nullptr;
+    TS_HIP(hipGetSymbolAddress(&found, HIP_SYMBOL(scratch)));
+    TS_REQUIRE(found != nullptr, TS_ERR_HIP, "ts_attention_decode_static: no device address for the scratch array");
+    g_scratch_ptr[dev] = found;
+  }
+  *out = g_scratch_ptr[dev];
+  return TS_OK;
+}
+}  // namespace
+
 }  // namespace ts
+
+extern "C" {
+
+size_t ts_attention_decode_static_limit(void) { return ts::kStaticScratchBytes; }
+
+int ts_attention_decode_static(const ts_bf16* q, const ts_bf16* kcache, const ts_bf16* vcache, const int32_t* seq_lens,
+                               ts_bf16* out, int B, int nq, int nkv, int d, int Lcap, float scale, void* stream) {
+  using namespace ts;
+  TS_REQUIRE(B >= 0 && nq > 0 && nkv > 0 && d > 0 && Lcap > 0, TS_ERR_INVALID_ARG,
+             "ts_attention_decode_static: B=%d nq=%d nkv=%d d=%d Lcap=%d", B, nq, nkv, d, Lcap);
+  TS_REQUIRE(nq % nkv == 0, TS_ERR_INVALID_ARG, "ts_attention_decode_static: nq %% nkv != 0");
+  TS_REQUIRE(B == 0 || (q && kcache && vcache && seq_lens && out), TS_ERR_INVALID_ARG, "ts_attention_decode_static: null pointer");
+  TS_REQUIRE(aligned16(q) && aligned16(kcache) && aligned16(vcache) && aligned16(out), TS_ERR_INVALID_ARG,
+             "ts_attention_decode_static: pointer not 16-byte aligned");
+  TS_REQUIRE(d == 64 || d == 128, TS_ERR_UNSUPPORTED_SHAPE, "ts_attention_decode_static: d=%d (64 or 128 supported)", d);
+  TS_REQUIRE(nq / nkv <= 16, TS_ERR_UNSUPPORTED_SHAPE, "ts_attention_decode_static: GQA group %d > 16", nq / nkv);
+  if (B == 0) return TS_OK;
+  const size_t need = attention_decode_workspace_bytes(B, nq, nkv, d, Lcap);
+  TS_REQUIRE(need <= kStaticScratchBytes, TS_ERR_WORKSPACE,
+             "ts_attention_decode_static: split-KV partials need %zu bytes, the built-in scratch holds %zu "
+             "(use ts_attention_decode with a workspace of your own)", need, kStaticScratchBytes);
+  void* ptr = nullptr;
+  int rc = static_scratch(&ptr);
+  if (rc != TS_OK) return rc;
+  // Nothing in the array has to start at zero: every partial a merge reads was written by this call's own split
+  // kernel (the arrival-counter form of the merge is not used here).
+  return launch_attention_decode(q, nq * d, kcache, vcache, seq_lens, out, B, nq, nkv, d, Lcap, scale, ptr,
+                                 kStaticScratchBytes, reinterpret_cast<hipStream_t>(stream), nullptr);
+}
+
+}  // extern "C"
