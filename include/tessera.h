@@ -474,6 +474,18 @@ typedef struct ts_plan_problem {
 int ts_plan_policy(const ts_plan_problem* problem, int objective, int64_t node_limit,
                    int32_t* placement, double* value, double* T_g, double* M_g,
                    int* proved_optimal);
+/* The same search with a stopping rule and its certificate.  It stops as soon as the placement found is within
+ * rel_gap (relative, in [0, 1); 0 = never) of a lower bound of the optimum that needs no search (the one
+ * ts_plan_lower_bound returns), which proves the placement optimal to that tolerance; the paper's solver call
+ * has the same kind of gap (Sec. 3.2, Sec. 5.4: about 500 kernels in 20 ms, 1500 in under a second).  Before and
+ * after the branch and bound a two-GPU throughput placement is balanced by moving whole classes of equal kernels
+ * (a decoder stack repeats a handful of shapes; Sec. 5.4 notes the same redundancy).
+ * *status: 2 = proved optimal (search finished), 1 = within rel_gap of *lower_bound, 0 = stopped by node_limit
+ * (the placement is valid and (value - *lower_bound) / value bounds its distance from the optimum).
+ * lower_bound and status may be NULL. */
+int ts_plan_policy_bounded(const ts_plan_problem* problem, int objective, int64_t node_limit, double rel_gap,
+                           int32_t* placement, double* value, double* T_g, double* M_g, double* lower_bound,
+                           int* status);
 /* A lower bound of the optimum of `objective` that needs no search: the sum over kernels of their fastest
  * time for the latency objective; for the throughput objective the larger of that sum divided by the number
  * of GPUs and, with two GPUs, the makespan of the best fractional split of the kernels without communication.

@@ -14,6 +14,14 @@ What it is:
   flow.  Cross-iteration dependencies are found the way the paper describes:
   the kernel list is run for two iterations and a read in the second iteration
   whose most recent writer ran in the first is flagged.
+* `plan_milp` -- the same two objectives as the mixed-integer linear programme the paper
+  hands to its solver (Sec. 3.2): binary x[k,g], one GPU per kernel, the product
+  y = x[i,u] x[j,g] of every edge replaced by a continuous y with y >= x[i,u] + x[j,g] - 1
+  (the standard linearisation; costs are non-negative and minimised, so the lower bound on y
+  is the only one that binds), T_g and M_g below a common W, minimise W (throughput), or
+  minimise sum t x + sum c y (latency).  scipy's MILP routine (HiGHS) serves as the solver,
+  a library step as the commercial solver is in the paper.  Used to check the product planner at
+  sizes where enumeration is impossible.
 * `policy_objective` / `plan_bruteforce` -- the two objectives of Sec. 3.2
   evaluated literally from their formulas (placement variables x, computation
   time T_g, communication time M_g with c = l + d / bw on cut edges, stage
@@ -38,7 +46,8 @@ Readings taken (the paper leaves them open):
       lands one position further in the second iteration.  An access may carry
       a fourth element, the bytes its range advances per iteration (default 0).
 
-Pins (tests/test_planner_pins.py): hand-worked graphs and placements, closed
+Pins (tests/test_planner_pins.py): `plan_milp` against `plan_bruteforce` on random
+problems; hand-worked graphs and placements, closed
 forms (free communication, prohibitive communication, one GPU, balanced
 partition), and for two GPUs the latency objective against a max-flow/min-cut
 computed by scipy (the objective is a submodular two-label energy).
@@ -145,3 +154,80 @@ def plan_bruteforce(t, edges, bw, lat, objective: str):
         if best is None or v < best:
             best, best_place = v, place
     return best, list(best_place)
+
+
+def plan_milp(t, edges: Dict[Tuple[int, int], float], bw, lat, objective: str, rel_gap: float = 1e-9,
+              time_limit: float = 120.0):
+    """The MILP of Sec. 3.2 solved by scipy.optimize.milp.
+
+    Returns (objective value of the placement found, placement, dual bound): the dual bound is the
+    solver's proven lower bound of the optimum (equal to the value up to rel_gap when it finishes).
+    """
+    import numpy as np
+    from scipy.optimize import Bounds, LinearConstraint, milp
+    from scipy.sparse import lil_matrix
+
+    n_k, n_g = len(t), len(t[0])
+    pairs = [(u, g) for u in range(n_g) for g in range(n_g) if u != g]
+    elist = list(edges.items())
+    # The solver works with absolute tolerances (about 1e-6 on the objective), so the programme is stated in
+    # units in which a kernel takes about 100: times in seconds of a few microseconds would be below them.
+    unit = 100.0 / max(1e-300, float(np.mean([max(row) for row in t])))
+    nx = n_k * n_g
+    ny = len(elist) * len(pairs)
+    n = nx + ny + 1                       # ... + W
+    X = lambda k, g: k * n_g + g
+    Y = lambda e, p: nx + e * len(pairs) + p
+    Wv = n - 1
+    cost = np.zeros(ny)
+    for e, ((i, j), d) in enumerate(elist):
+        for p, (u, g) in enumerate(pairs):
+            cost[e * len(pairs) + p] = transfer_cost(d, u, g, bw, lat) * unit
+    rows, lo, hi = [], [], []
+    A = lil_matrix((n_k + ny + 2 * n_g, n))
+    r = 0
+    for k in range(n_k):                  # one GPU per kernel
+        for g in range(n_g):
+            A[r, X(k, g)] = 1.0
+        lo.append(1.0); hi.append(1.0); r += 1
+    for e, ((i, j), d) in enumerate(elist):   # y >= x_iu + x_jg - 1
+        for p, (u, g) in enumerate(pairs):
+            A[r, X(i, u)] = 1.0
+            A[r, X(j, g)] = 1.0
+            A[r, Y(e, p)] = -1.0
+            lo.append(-np.inf); hi.append(1.0); r += 1
+    c = np.zeros(n)
+    if objective == "throughput":
+        for g in range(n_g):              # T_g <= W
+            for k in range(n_k):
+                A[r, X(k, g)] = t[k][g] * unit
+            A[r, Wv] = -1.0
+            lo.append(-np.inf); hi.append(0.0); r += 1
+        for g in range(n_g):              # M_g <= W
+            for e in range(len(elist)):
+                for p, (u, gg) in enumerate(pairs):
+                    if gg == g:
+                        A[r, Y(e, p)] = cost[e * len(pairs) + p]
+            A[r, Wv] = -1.0
+            lo.append(-np.inf); hi.append(0.0); r += 1
+        c[Wv] = 1.0
+    elif objective == "latency":
+        for k in range(n_k):
+            for g in range(n_g):
+                c[X(k, g)] = t[k][g] * unit
+        c[nx:nx + ny] = cost
+    else:
+        raise ValueError(objective)
+    A = A[:r].tocsr()
+    integrality = np.zeros(n)
+    integrality[:nx] = 1
+    ub = np.ones(n)
+    ub[Wv] = np.inf
+    res = milp(c, constraints=LinearConstraint(A, np.array(lo), np.array(hi)), integrality=integrality,
+               bounds=Bounds(np.zeros(n), ub), options={"mip_rel_gap": rel_gap, "time_limit": time_limit})
+    if res.x is None:
+        raise RuntimeError(f"MILP not solved: {res.message}")
+    place = [int(np.argmax(res.x[k * n_g:(k + 1) * n_g])) for k in range(n_k)]
+    value = policy_objective(place, t, edges, bw, lat, n_g, objective)
+    bound = getattr(res, "mip_dual_bound", None)
+    return value, place, (float(bound) if bound is not None else float(res.fun)) / unit

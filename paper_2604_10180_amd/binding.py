@@ -27,7 +27,7 @@ EXPORTS = [
     "ts_layer_workspace_bytes", "ts_layer_boundary", "ts_layer_moe_buffers", "ts_layer_node_accesses", "ts_layer_forward",
     "ts_pipeline_create", "ts_pipeline_destroy", "ts_pipeline_boundary_layout", "ts_pipeline_slot_stride",
     "ts_pipeline_workspace_slot_bytes",
-    "ts_pipeline_step", "ts_pipeline_kv_delta_stride", "ts_pipeline_set_kv_delta", "ts_pipeline_set_link_slowdown", "ts_ddg_build", "ts_layer_ddg", "ts_layer_node_name", "ts_layer_cut_mask", "ts_plan_policy", "ts_plan_lower_bound",
+    "ts_pipeline_step", "ts_pipeline_kv_delta_stride", "ts_pipeline_set_kv_delta", "ts_pipeline_set_link_slowdown", "ts_ddg_build", "ts_layer_ddg", "ts_layer_node_name", "ts_layer_cut_mask", "ts_plan_policy", "ts_plan_policy_bounded", "ts_plan_lower_bound",
     "ts_monitor_create", "ts_monitor_destroy", "ts_monitor_record", "ts_monitor_advance",
 ]
 
@@ -146,6 +146,9 @@ lib.ts_layer_node_name.argtypes = [C.POINTER(LayerDesc), _i]
 lib.ts_layer_cut_mask.argtypes = [C.POINTER(LayerDesc), C.POINTER(C.c_int32), C.POINTER(_u64)]
 lib.ts_plan_policy.argtypes = [C.POINTER(PlanProblem), _i, C.c_int64, C.POINTER(C.c_int32), C.POINTER(C.c_double),
                                C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(_i)]
+lib.ts_plan_policy_bounded.argtypes = [C.POINTER(PlanProblem), _i, C.c_int64, C.c_double, C.POINTER(C.c_int32),
+                                       C.POINTER(C.c_double), C.POINTER(C.c_double), C.POINTER(C.c_double),
+                                       C.POINTER(C.c_double), C.POINTER(_i)]
 lib.ts_plan_lower_bound.argtypes = [C.POINTER(PlanProblem), _i, C.POINTER(C.c_double)]
 lib.ts_monitor_create.argtypes = [C.c_double, C.c_double, _i, C.POINTER(_p)]
 lib.ts_monitor_destroy.argtypes = [_p]
@@ -446,6 +449,18 @@ def ts_plan_policy(t, edges, bw, lat, objective: int, node_limit: int = 0):
     Tg, Mg = (C.c_double * G)(), (C.c_double * G)()
     _check(lib.ts_plan_policy(C.byref(prob), objective, node_limit, place, C.byref(val), Tg, Mg, C.byref(opt)))
     return list(place), val.value, list(Tg), list(Mg), bool(opt.value)
+
+
+def ts_plan_policy_bounded(t, edges, bw, lat, objective: int, rel_gap: float, node_limit: int = 0):
+    """Returns (placement, value, T_g, M_g, lower_bound, status); status 2 = optimal, 1 = within rel_gap of the
+    lower bound, 0 = stopped by the node limit."""
+    K, G = len(t), len(t[0])
+    prob, _keep = _plan_problem(t, edges, bw, lat)
+    place, val, lb, st = (C.c_int32 * K)(), C.c_double(), C.c_double(), _i()
+    Tg, Mg = (C.c_double * G)(), (C.c_double * G)()
+    _check(lib.ts_plan_policy_bounded(C.byref(prob), objective, node_limit, rel_gap, place, C.byref(val), Tg, Mg,
+                                      C.byref(lb), C.byref(st)))
+    return list(place), val.value, list(Tg), list(Mg), lb.value, st.value
 
 
 def ts_monitor_create(window_s: float = 0.3, beta: float = 1.5, initial_policy: int = TS_PLAN_LATENCY) -> int:

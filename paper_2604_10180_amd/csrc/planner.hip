@@ -21,6 +21,7 @@
 #include <cmath>
 #include <limits>
 #include <map>
+#include <tuple>
 #include <unordered_map>
 #include <utility>
 #include <vector>
@@ -240,6 +241,10 @@ struct BnB {
   int objective;
   int64_t node_limit, nodes = 0;
   bool exhausted = false;
+  // stop as soon as the incumbent is within rel_gap of `root_lb`, a lower bound of the optimum (0: never)
+  double rel_gap = 0.0, root_lb = 0.0;
+  bool within_gap = false;
+  bool close_enough() const { return rel_gap > 0.0 && best <= root_lb * (1.0 + rel_gap); }
   std::vector<double> T, M, rem_min;          // rem_min[k] = sum_{j >= k} min_g t[j][g]
   std::vector<int32_t> place, best_place;
   double best = std::numeric_limits<double>::infinity();
@@ -263,9 +268,49 @@ struct BnB {
   // communication) bounds every integral completion from below.  Start with all of them on GPU 0 and move
   // them over in ascending order of (time on GPU 1) / (time on GPU 0) until the two loads meet.
   std::vector<int> by_ratio;                   // all kernels, ascending t[k][1] / t[k][0]
+  // The same walk in O(log K): for every suffix k the kernels j >= k in ratio order with running sums of their
+  // times (built once, K^2 / 2 entries per table; used up to kFracTableMax kernels, the linear walk beyond).
+  // The running sums round differently from the walk, so the result is lowered by a relative 1e-13: a bound
+  // only has to stay below the truth.
+  static constexpr int kFracTableMax = 2048;
+  std::vector<size_t> frac_begin;                      // [K+1] start of suffix k's list
+  std::vector<double> frac_a, frac_b;                  // per entry: that kernel's time on GPU 0 / GPU 1
+  std::vector<double> frac_sa, frac_sb, frac_sab;      // running sums up to and including the entry
+  void build_fractional_tables() {
+    const int K = p.K;
+    if (p.G != 2 || K > kFracTableMax) return;
+    frac_begin.assign(K + 1, 0);
+    size_t total = 0;
+    for (int k = 0; k <= K; ++k) { frac_begin[k] = total; total += (size_t)(K - k); }
+    frac_a.resize(total); frac_b.resize(total); frac_sa.resize(total); frac_sb.resize(total); frac_sab.resize(total);
+    std::vector<size_t> fill(frac_begin.begin(), frac_begin.end() - 1);
+    for (int j : by_ratio) {
+      const double a = p.t[j * 2], b = p.t[j * 2 + 1];
+      for (int k = 0; k <= j; ++k) {                   // kernel j belongs to every suffix k <= j
+        const size_t at = fill[k]++;
+        const bool first = at == frac_begin[k];
+        frac_a[at] = a; frac_b[at] = b;
+        frac_sa[at] = (first ? 0.0 : frac_sa[at - 1]) + a;
+        frac_sb[at] = (first ? 0.0 : frac_sb[at - 1]) + b;
+        frac_sab[at] = frac_sa[at] + frac_sb[at];
+      }
+    }
+  }
   double two_gpu_fractional(int k) const {
     double L0 = T[0] + rem0[k], L1 = T[1];
     if (L1 >= L0) return L1;
+    if (!frac_begin.empty()) {
+      // entry i can be moved whole (after the entries before it) iff L1 + sb[i] <= L0 - sa[i]
+      const size_t lo = frac_begin[k], hi = frac_begin[k + 1];
+      const double diff = L0 - L1;
+      const size_t m = (size_t)(std::upper_bound(frac_sab.begin() + lo, frac_sab.begin() + hi, diff) - (frac_sab.begin() + lo));
+      if (m > 0) { L0 -= frac_sa[lo + m - 1]; L1 += frac_sb[lo + m - 1]; }
+      const double slack = 1.0 - 1e-13;
+      if (m == hi - lo) return std::max(L0, L1) * slack;
+      const double a = frac_a[lo + m], b = frac_b[lo + m];
+      if (a <= 0.0) return std::max(L0, L1) * slack;   // nothing left that relieves GPU 0
+      return (L1 + (L0 - L1) / (a + b) * b) * slack;   // the fraction of that kernel that makes the loads equal
+    }
     for (int j : by_ratio) {
       if (j < k) continue;
       const double a = p.t[j * 2], b = p.t[j * 2 + 1];
@@ -282,7 +327,11 @@ struct BnB {
     if (++nodes > node_limit) { exhausted = true; return; }
     if (k == p.K) {
       const double v = bound(k);
-      if (v < best) { best = v; best_place = place; }
+      if (v < best) {
+        best = v;
+        best_place = place;
+        if (close_enough()) { within_gap = true; exhausted = true; }   // good enough: unwind
+      }
       return;
     }
     // children ordered by their bound
@@ -309,6 +358,179 @@ struct BnB {
       dfs(k + 1);
       T[g] = t0; M[g] = m0;                    // restore exactly (no accumulated rounding)
     }
+  }
+};
+
+
+// Two GPUs, throughput objective: fine balancing of a placement.  The search above dives in execution order and
+// can only revise its late decisions, and a decoder stack repeats a handful of kernel shapes, so the loads
+// (T_0, T_1) it reaches are a coarse subset of what is reachable.  This step looks at whole classes of equal
+// kernels instead: a class is (current GPU, time on GPU 0, time on GPU 1); moving c kernels of a class to the
+// other GPU changes the loads by c * (-a, +b) or c * (+a, -b).  The classes are cut into two halves, every
+// combination of counts (0 .. a small window) is enumerated per half, and the halves are joined through the
+// Pareto front of one of them: the best combinations by max(T_0, T_1) are then applied (members of a class
+// are taken in the order of what the move adds to the communication terms) and evaluated exactly, communication
+// included; the placement is replaced only by a strictly better one.
+struct Polish {
+  const Problem& p;
+  std::vector<std::vector<int>> outs;                       // consumers of every kernel (the problem stores producers)
+
+  explicit Polish(const Problem& pr) : p(pr), outs(pr.K) {
+    for (int k = 0; k < p.K; ++k)
+      for (const auto& e : p.in[k]) outs[e.first].push_back(k);
+  }
+  static double objective_of(const std::vector<double>& T, const std::vector<double>& M) {
+    double v = 0.0;
+    for (size_t g = 0; g < T.size(); ++g) v = std::max(v, std::max(T[g], M[g]));
+    return v;
+  }
+  // what flipping kernel k alone adds to M_0 + M_1 under `place`
+  double flip_comm_delta(const std::vector<int32_t>& place, int k) const {
+    const int g = place[k], h = 1 - g;
+    double d = 0.0;
+    for (const auto& e : p.in[k]) {
+      const int u = place[e.first];
+      if (u != g) d -= p.cost(u, g, e.second);
+      if (u != h) d += p.cost(u, h, e.second);
+    }
+    for (int j : outs[k]) {
+      const int gj = place[j];
+      for (const auto& e : p.in[j])
+        if (e.first == k) {
+          if (g != gj) d -= p.cost(g, gj, e.second);
+          if (h != gj) d += p.cost(h, gj, e.second);
+        }
+    }
+    return d;
+  }
+  struct Class { double a, b; std::vector<int> on0, on1; int lo = 0, hi = 0; };   // count range: lo <= 0 <= hi
+  struct Combo { double d0, d1; uint32_t code; };
+
+  bool run(std::vector<int32_t>& place, double& value) const {
+    if (p.G != 2 || p.K < 2) return false;
+    std::vector<double> T, M;
+    evaluate(p, place.data(), T, M);
+    // classes of kernels with equal times; a count c > 0 moves c members from GPU 0 to GPU 1, c < 0 the other way:
+    // the loads change by (-c a, +c b) either way
+    std::map<std::pair<double, double>, int> index;
+    std::vector<Class> cls;
+    for (int k = 0; k < p.K; ++k) {
+      const auto key = std::make_pair(p.t[k * 2], p.t[k * 2 + 1]);
+      auto it = index.find(key);
+      if (it == index.end()) {
+        it = index.emplace(key, (int)cls.size()).first;
+        cls.push_back(Class{key.first, key.second, {}, {}});
+      }
+      (place[k] == 0 ? cls[it->second].on0 : cls[it->second].on1).push_back(k);
+    }
+    std::vector<double> cheapest(cls.size(), std::numeric_limits<double>::infinity());
+    for (size_t c = 0; c < cls.size(); ++c) {
+      for (auto* m : {&cls[c].on0, &cls[c].on1}) {
+        std::vector<std::pair<double, int>> by_cost;
+        for (int k : *m) by_cost.push_back({flip_comm_delta(place, k), k});
+        std::sort(by_cost.begin(), by_cost.end());
+        for (size_t i = 0; i < m->size(); ++i) (*m)[i] = by_cost[i].second;
+        if (!by_cost.empty()) cheapest[c] = std::min(cheapest[c], by_cost[0].first);
+      }
+    }
+    // digits: classes in the order of their cheapest move, counts in a window around 0 sized so that each of the
+    // two halves has at most 2^16 combinations
+    std::vector<int> order(cls.size());
+    for (size_t c = 0; c < cls.size(); ++c) order[c] = (int)c;
+    std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return cheapest[x] < cheapest[y]; });
+    const size_t cap = (size_t)1 << 16;
+    const size_t per_half = (cls.size() + 1) / 2;
+    int window = 1;
+    while (window < 31 && std::pow((double)(2 * (window + 1) + 1), (double)std::min<size_t>(per_half, 16)) <= (double)cap) ++window;
+    std::vector<int> half[2];
+    std::vector<int> radix[2];
+    size_t prod[2] = {1, 1};
+    for (int c : order) {
+      if (cls[c].a <= 0.0 && cls[c].b <= 0.0) continue;
+      cls[c].hi = std::min<int>(window, (int)cls[c].on0.size());
+      cls[c].lo = -std::min<int>(window, (int)cls[c].on1.size());
+      const int r = cls[c].hi - cls[c].lo + 1;
+      const int h = prod[0] <= prod[1] ? 0 : 1;
+      if (r < 2 || prod[h] * (size_t)r > cap) continue;
+      half[h].push_back(c);
+      radix[h].push_back(r);
+      prod[h] *= (size_t)r;
+    }
+    if (half[0].empty() && half[1].empty()) return false;
+    auto enumerate = [&](int h, std::vector<Combo>& out) {
+      out.assign(prod[h], Combo{0.0, 0.0, 0});
+      for (size_t code = 0; code < prod[h]; ++code) {
+        size_t rest = code;
+        double d0 = 0.0, d1 = 0.0;
+        for (size_t i = 0; i < half[h].size(); ++i) {
+          const Class& c = cls[half[h][i]];
+          const int cnt = c.lo + (int)(rest % (size_t)radix[h][i]);
+          rest /= (size_t)radix[h][i];
+          d0 -= cnt * c.a;
+          d1 += cnt * c.b;
+        }
+        out[code] = Combo{d0, d1, (uint32_t)code};
+      }
+    };
+    std::vector<Combo> left, right;
+    enumerate(0, left);
+    enumerate(1, right);
+    // Pareto front of the right half: ascending d0, strictly descending d1
+    std::sort(right.begin(), right.end(), [](const Combo& x, const Combo& y) { return x.d0 < y.d0 || (x.d0 == y.d0 && x.d1 < y.d1); });
+    std::vector<Combo> front;
+    for (const Combo& c : right)
+      if (front.empty() || c.d1 < front.back().d1) front.push_back(c);
+    // best joins by max(T_0, T_1)
+    struct Cand { double f; uint32_t l, r; };
+    std::vector<Cand> cands;
+    const size_t keep = 48;
+    double worst_kept = std::numeric_limits<double>::infinity();
+    auto offer = [&](double f, uint32_t l, uint32_t r) {
+      if (cands.size() >= keep && f >= worst_kept) return;
+      cands.push_back(Cand{f, l, r});
+      if (cands.size() >= 4 * keep) {
+        std::nth_element(cands.begin(), cands.begin() + keep, cands.end(), [](const Cand& x, const Cand& y) { return x.f < y.f; });
+        cands.resize(keep);
+        worst_kept = 0.0;
+        for (const Cand& c : cands) worst_kept = std::max(worst_kept, c.f);
+      }
+    };
+    for (const Combo& l : left) {
+      const double t0 = T[0] + l.d0, t1 = T[1] + l.d1;
+      // first front entry where GPU 0 is at least as loaded as GPU 1 (t0 + d0 grows, t1 + d1 falls along the front)
+      size_t lo = 0, hi = front.size();
+      while (lo < hi) {
+        const size_t mid = (lo + hi) / 2;
+        if (t0 + front[mid].d0 >= t1 + front[mid].d1) hi = mid; else lo = mid + 1;
+      }
+      for (size_t i = (lo > 0 ? lo - 1 : 0); i < std::min(front.size(), lo + 2); ++i)
+        offer(std::max(t0 + front[i].d0, t1 + front[i].d1), l.code, front[i].code);
+    }
+    std::sort(cands.begin(), cands.end(), [](const Cand& x, const Cand& y) { return x.f < y.f; });
+    if (cands.size() > keep) cands.resize(keep);
+    bool improved = false;
+    const std::vector<int32_t> base = place;    // the classes and their member order refer to this placement
+    std::vector<int32_t> trial;
+    std::vector<double> Tt, Mt;
+    for (const Cand& c : cands) {
+      if (c.f >= value) break;                  // even without communication it would not beat the incumbent
+      trial = base;
+      const uint32_t codes[2] = {c.l, c.r};
+      for (int h = 0; h < 2; ++h) {
+        size_t rest = codes[h];
+        for (size_t i = 0; i < half[h].size(); ++i) {
+          const Class& k = cls[half[h][i]];
+          const int cnt = k.lo + (int)(rest % (size_t)radix[h][i]);
+          rest /= (size_t)radix[h][i];
+          for (int q = 0; q < cnt; ++q) trial[k.on0[q]] = 1;
+          for (int q = 0; q < -cnt; ++q) trial[k.on1[q]] = 0;
+        }
+      }
+      evaluate(p, trial.data(), Tt, Mt);
+      const double v = objective_of(Tt, Mt);
+      if (v < value) { value = v; place = trial; improved = true; }
+    }
+    return improved;
   }
 };
 
@@ -467,9 +689,10 @@ int ts_layer_cut_mask(const ts_layer_desc* desc, const int32_t* placement, uint6
   return TS_OK;
 }
 
-// Shared by the two planner entry points: validates, searches, and reports a lower bound of the optimum.
-static int plan_impl(const ts_plan_problem* pr, int objective, int64_t node_limit, int32_t* placement, double* value,
-                     double* T_g, double* M_g, int* proved_optimal, double* lower_bound, const char* who) {
+// Shared by the planner entry points: validates, searches, and reports a lower bound of the optimum.
+// status: 2 = proved optimal, 1 = within rel_gap of the lower bound (proved by that bound), 0 = stopped by the node limit.
+static int plan_impl(const ts_plan_problem* pr, int objective, int64_t node_limit, double rel_gap, int32_t* placement,
+                     double* value, double* T_g, double* M_g, int* status, double* lower_bound, const char* who) {
   TS_REQUIRE(pr != nullptr, TS_ERR_INVALID_ARG, "%s: null problem", who);
   TS_REQUIRE(pr->n_kernels >= 1 && pr->n_gpus >= 1 && pr->n_gpus <= 64 && pr->n_edges >= 0, TS_ERR_INVALID_ARG,
              "%s: bad sizes (kernels %d, gpus %d, edges %d)", who, pr->n_kernels, pr->n_gpus, pr->n_edges);
@@ -477,6 +700,7 @@ static int plan_impl(const ts_plan_problem* pr, int objective, int64_t node_limi
              TS_ERR_INVALID_ARG, "%s: null table", who);
   TS_REQUIRE(objective == TS_PLAN_THROUGHPUT || objective == TS_PLAN_LATENCY, TS_ERR_INVALID_ARG,
              "%s: unknown objective %d", who, objective);
+  TS_REQUIRE(rel_gap >= 0.0 && rel_gap < 1.0, TS_ERR_INVALID_ARG, "%s: rel_gap %g outside [0, 1)", who, rel_gap);
   Problem p;
   p.K = pr->n_kernels;
   p.G = pr->n_gpus;
@@ -513,6 +737,7 @@ static int plan_impl(const ts_plan_problem* pr, int objective, int64_t node_limi
       return p.t[x * 2] > 0.0 ? p.t[x * 2 + 1] / p.t[x * 2] : std::numeric_limits<double>::infinity();
     };
     std::stable_sort(s.by_ratio.begin(), s.by_ratio.end(), [&](int x, int y) { return ratio(x) < ratio(y); });
+    if (objective == TS_PLAN_THROUGHPUT && placement != nullptr) s.build_fractional_tables();
   }
   const double root_bound = s.bound(0);                    // nothing placed yet: a bound of the optimum itself
   if (placement == nullptr) {                              // bound only
@@ -522,8 +747,10 @@ static int plan_impl(const ts_plan_problem* pr, int objective, int64_t node_limi
 
   std::vector<int32_t> best_place;
   double best = 0.0;
-  bool optimal = true;
+  int st = 2;
   if (!(objective == TS_PLAN_LATENCY && plan_latency_dp(p, best_place, best))) {
+    s.rel_gap = rel_gap;
+    s.root_lb = root_bound;
     // incumbent: the best single GPU (always feasible, no communication)
     for (int g = 0; g < p.G; ++g) {
       double v = 0.0;
@@ -541,9 +768,22 @@ static int plan_impl(const ts_plan_problem* pr, int objective, int64_t node_limi
       s.T.assign(p.G, 0.0);
       s.M.assign(p.G, 0.0);
     }
-    s.dfs(0);
+    // two GPUs, throughput: balance the incumbent by whole classes of equal kernels before and after the search
+    const bool polish = objective == TS_PLAN_THROUGHPUT && p.G == 2;
+    Polish fine(p);
+    auto polish_rounds = [&]() {
+      for (int round = 0; polish && round < 6 && !s.close_enough(); ++round)
+        if (!fine.run(s.best_place, s.best)) break;
+    };
+    polish_rounds();
+    bool complete = false;                               // the branch and bound ran to its end
+    if (!s.close_enough()) {
+      s.dfs(0);
+      complete = !s.exhausted;
+      if (!complete && !s.within_gap) polish_rounds();
+    }
     best_place = s.best_place;
-    optimal = !s.exhausted;
+    st = complete ? 2 : (s.close_enough() ? 1 : 0);
   }
   std::vector<double> T, M;
   evaluate(p, best_place.data(), T, M);
@@ -558,20 +798,31 @@ static int plan_impl(const ts_plan_problem* pr, int objective, int64_t node_limi
   *value = v;
   if (T_g) std::copy(T.begin(), T.end(), T_g);
   if (M_g) std::copy(M.begin(), M.end(), M_g);
-  if (proved_optimal) *proved_optimal = optimal ? 1 : 0;
-  if (lower_bound) *lower_bound = optimal ? v : std::min(v, root_bound);
+  if (status) *status = st;
+  if (lower_bound) *lower_bound = st == 2 ? v : std::min(v, root_bound);
   return TS_OK;
 }
 
 int ts_plan_policy(const ts_plan_problem* pr, int objective, int64_t node_limit, int32_t* placement, double* value,
                    double* T_g, double* M_g, int* proved_optimal) {
   TS_REQUIRE(placement != nullptr && value != nullptr, TS_ERR_INVALID_ARG, "ts_plan_policy: null argument");
-  return plan_impl(pr, objective, node_limit, placement, value, T_g, M_g, proved_optimal, nullptr, "ts_plan_policy");
+  int st = 0;
+  int rc = plan_impl(pr, objective, node_limit, 0.0, placement, value, T_g, M_g, &st, nullptr, "ts_plan_policy");
+  if (rc == TS_OK && proved_optimal) *proved_optimal = st == 2 ? 1 : 0;
+  return rc;
+}
+
+int ts_plan_policy_bounded(const ts_plan_problem* pr, int objective, int64_t node_limit, double rel_gap,
+                           int32_t* placement, double* value, double* T_g, double* M_g, double* lower_bound,
+                           int* status) {
+  TS_REQUIRE(placement != nullptr && value != nullptr, TS_ERR_INVALID_ARG, "ts_plan_policy_bounded: null argument");
+  return plan_impl(pr, objective, node_limit, rel_gap, placement, value, T_g, M_g, status, lower_bound,
+                   "ts_plan_policy_bounded");
 }
 
 int ts_plan_lower_bound(const ts_plan_problem* pr, int objective, double* lower_bound) {
   TS_REQUIRE(lower_bound != nullptr, TS_ERR_INVALID_ARG, "ts_plan_lower_bound: null argument");
-  return plan_impl(pr, objective, 0, nullptr, nullptr, nullptr, nullptr, nullptr, lower_bound, "ts_plan_lower_bound");
+  return plan_impl(pr, objective, 0, 0.0, nullptr, nullptr, nullptr, nullptr, nullptr, lower_bound, "ts_plan_lower_bound");
 }
 
 }  // extern "C"

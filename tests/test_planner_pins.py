@@ -187,3 +187,30 @@ def test_two_gpu_latency_objective_is_a_minimum_cut():
             cap[j, i] += int(v)
         flow = maximum_flow(csr_matrix(cap), n, n + 1).flow_value
         assert best == pytest.approx(float(flow))
+
+
+@pytest.mark.parametrize("objective", ["throughput", "latency"])
+def test_milp_formulation_attains_the_bruteforce_optimum(objective):
+    """The mixed-integer programme of Sec. 3.2 (binary placements, linearised edge products, W above every T_g
+    and M_g) handed to a solver gives what enumeration gives: pins `plan_milp`, the reference at sizes that
+    cannot be enumerated."""
+    import numpy as np
+    rng = np.random.default_rng(5)
+    for trial in range(6):
+        nk, ng = 6 + trial % 3, 2 + trial % 2
+        t = [[float(rng.uniform(1, 10)) for _ in range(ng)] for _ in range(nk)]
+        edges = {(i, j): float(rng.uniform(1, 50)) for i in range(nk) for j in range(i + 1, nk) if rng.random() < 0.35}
+        bw = [[float("inf") if a == b else float(rng.uniform(5, 20)) for b in range(ng)] for a in range(ng)]
+        lat = [[0.0 if a == b else float(rng.uniform(0, 1)) for b in range(ng)] for a in range(ng)]
+        best, _ = P.plan_bruteforce(t, edges, bw, lat, objective)
+        value, place, bound = P.plan_milp(t, edges, bw, lat, objective)
+        assert value == pytest.approx(best, rel=1e-9)
+        assert bound <= value * (1 + 1e-9) and bound >= best * (1 - 1e-6)
+        assert P.policy_objective(place, t, edges, bw, lat, ng, objective) == pytest.approx(value)
+    # times of a few microseconds (below the solver's absolute tolerances unless the programme is rescaled)
+    t = [[3e-6, 9e-6], [5e-6, 6e-6], [4e-6, 4e-6], [7e-6, 30e-6], [2e-6, 2.5e-6]]
+    edges = {(0, 1): 1e5, (1, 2): 2e5, (2, 3): 1e5, (0, 4): 5e4}
+    bw = [[float("inf"), 25e9], [25e9, float("inf")]]
+    lat = [[0.0, 1e-7], [1e-7, 0.0]]
+    best, _ = P.plan_bruteforce(t, edges, bw, lat, objective)
+    assert P.plan_milp(t, edges, bw, lat, objective)[0] == pytest.approx(best, rel=1e-9)
