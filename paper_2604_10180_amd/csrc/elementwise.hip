@@ -16,7 +16,13 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* x, const uint
   if (row == 0)
     for (int i = tid; i < nzero; i += 256) zero[i] = 0;
   const uint4* xr = x + (size_t)row * H8;
-  U4 v[VPT];
+  U4 v[VPT], gm[VPT];
+  // the gains do not depend on the reduction: their loads travel together with the row's
+#pragma unroll
+  for (int i = 0; i < VPT; ++i) {
+    int c = tid + i * 256;
+    if (c < H8) gm[i].u = gamma[c];
+  }
   float ss = 0.f;
 #pragma unroll
   for (int i = 0; i < VPT; ++i) {
@@ -42,7 +48,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const uint4* x, const uint
     int c = tid + i * 256;
     if (c < H8) {
       U4 g, o;
-      g.u = gamma[c];
+      g.u = gm[i].u;
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         float a = bf_lo(v[i].w[j]) * rs * bf_lo(g.w[j]);

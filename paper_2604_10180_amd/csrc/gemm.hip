@@ -299,23 +299,48 @@ __global__ __launch_bounds__(64 * WAVES) void gemm_skinny_kernel(SkinnyArgs a) {
   }
 }
 
-// out[m,n] = sum_s partial[s,m,n] (+ residual), slices added in ascending s (deterministic).
+// out[m,n] = sum_s partial[s,m,n] (+ residual), slices added in ascending s (deterministic).  A thread owns two
+// consecutive elements of the flattened [M*N] result; the loads of four slices are in flight together (the
+// slices are independent addresses, a loop of dependent loads would pay the memory latency S times).  An odd
+// element count (possible only for an fp32 result with odd N) leaves a last single element.
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ partial,
                                                             const ts_bf16* __restrict__ residual, void* C, long MN,
                                                             int S, int f32out) {
-  long i = ((long)blockIdx.x * 256 + threadIdx.x) * 2;
+  const long i = ((long)blockIdx.x * 256 + threadIdx.x) * 2;
   if (i >= MN) return;
+  if (i + 1 >= MN) {   // odd tail
+    float a0 = 0.f;
+    for (int s = 0; s < S; ++s) a0 += partial[(size_t)s * MN + i];
+    if (f32out) reinterpret_cast<float*>(C)[i] = a0;
+    else reinterpret_cast<ts_bf16*>(C)[i] = f_to_bf(residual != nullptr ? a0 + bf_to_f(residual[i]) : a0);
+    return;
+  }
+  const bool even = (MN & 1) == 0;   // rows keep 8-byte alignment only then
+  auto ld2 = [&](int s) {
+    const float* p = partial + (size_t)s * MN + i;
+    return even ? *reinterpret_cast<const float2*>(p) : make_float2(p[0], p[1]);
+  };
   float a0 = 0.f, a1 = 0.f;
-  for (int s = 0; s < S; ++s) {
-    float2 p = *reinterpret_cast<const float2*>(partial + (size_t)s * MN + i);
+  int s = 0;
+  for (; s + 4 <= S; s += 4) {
+    const float2 p0 = ld2(s), p1 = ld2(s + 1), p2 = ld2(s + 2), p3 = ld2(s + 3);
+    a0 += p0.x; a1 += p0.y;
+    a0 += p1.x; a1 += p1.y;
+    a0 += p2.x; a1 += p2.y;
+    a0 += p3.x; a1 += p3.y;
+  }
+  for (; s < S; ++s) {
+    const float2 p = ld2(s);
     a0 += p.x;
     a1 += p.y;
   }
   if (f32out) {
-    *reinterpret_cast<float2*>(reinterpret_cast<float*>(C) + i) = make_float2(a0, a1);
+    float* c = reinterpret_cast<float*>(C) + i;
+    c[0] = a0;
+    c[1] = a1;
     return;
   }
-  if (residual != nullptr) {
+  if (residual != nullptr) {   // bf16 results have an even N (checked at the boundary): pairs are 4-byte aligned
     uint32_t r = *reinterpret_cast<const uint32_t*>(residual + i);
     a0 += bf_lo(r);
     a1 += bf_hi(r);
@@ -671,7 +696,7 @@ int launch_tiled(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, vo
   TS_LAUNCH_CHECK("gemm_tiled");
   if (partial != nullptr) {
     const long MN = (long)M * N;
-    TS_LAUNCH_LAST("splitk_reduce", splitk_reduce_kernel, dim3((unsigned)((MN / 2 + 255) / 256)), dim3(256), 0, s, partial,
+    TS_LAUNCH_LAST("splitk_reduce", splitk_reduce_kernel, dim3((unsigned)(((MN + 1) / 2 + 255) / 256)), dim3(256), 0, s, partial,
               residual, C, MN, S, f32out ? 1 : 0);
     TS_LAUNCH_CHECK("splitk_reduce");
   }
@@ -709,7 +734,7 @@ int launch_gemm(const ts_bf16* A, const ts_bf16* W, const ts_bf16* residual, voi
     TS_LAUNCH_CHECK("gemm_skinny");
     if (p.S > 1) {
       long MN = (long)M * N;
-      TS_LAUNCH_LAST("splitk_reduce", splitk_reduce_kernel, dim3((unsigned)((MN / 2 + 255) / 256)), dim3(256), 0, s,
+      TS_LAUNCH_LAST("splitk_reduce", splitk_reduce_kernel, dim3((unsigned)(((MN + 1) / 2 + 255) / 256)), dim3(256), 0, s,
                          reinterpret_cast<const float*>(ws), residual, C, MN, p.S, f32out ? 1 : 0);
       TS_LAUNCH_CHECK("splitk_reduce");
     }

@@ -46,9 +46,6 @@ typedef __attribute__((address_space(3))) void lds_void;
 // those reads wait for the loads in flight.
 __shared__ uint4 g_stage0[kStageU4];
 __shared__ uint4 g_stage1[kStageU4];
-#ifndef TS_GEMM_PF
-#define TS_GEMM_PF 1
-#endif
 
 __device__ __forceinline__ void wait_vm0() { __builtin_amdgcn_s_waitcnt(0x0F70); }  // vmcnt(0) only
 // Workgroup barrier without the counter waits that __syncthreads() adds (it would wait for every load in
@@ -125,7 +122,7 @@ __device__ __forceinline__ void gemm_mfma256_body(const ts_bf16* __restrict__ A,
   // compiler's own counter bookkeeping stays exact); lanes 12..63 repeat lane 11's address.
   uint32_t warm_prev = 0;
   auto warm_l2 = [&](int k0) -> uint32_t {
-    return TS_GEMM_PF ? *reinterpret_cast<const uint32_t*>(pfbase + (size_t)k0 * 2) : 0u;
+    return *reinterpret_cast<const uint32_t*>(pfbase + (size_t)k0 * 2);
   };
   // load pair h (0..3) of a K step: one W and one A instruction of this wave
   auto issue_pair = [&](uint4* stage, int k0, int h) {
@@ -229,7 +226,7 @@ __device__ __forceinline__ void gemm_mfma256_body(const ts_bf16* __restrict__ A,
     order(R4{});
     __builtin_amdgcn_sched_barrier(0);
     // the next stage has landed (all but the newest load, the warm-up) and this one is fully read
-    __builtin_amdgcn_s_waitcnt(TS_GEMM_PF ? 0x0071 : 0x0070);
+    __builtin_amdgcn_s_waitcnt(0x0071);
     ring_barrier();
     asm volatile("" ::"v"(warm_prev));   // the previous step's warm-up word has arrived by now
     warm_prev = warm;

@@ -148,8 +148,11 @@ def test_prefill_layer_with_the_activation_in_the_projection_epilogue(B):
     assert np.all(diff <= tol)
 
 
-def test_small_moe_layer_teacher_forced(B):
-    shape = WL.LayerShape(H=512, nq=8, nkv=2, d=64, F=688, E=8, k=2)
+@pytest.mark.parametrize("E", [8, 17])
+def test_small_moe_layer_teacher_forced(B, E):
+    """E = 17: more experts than the router kernel takes, so the logits come from the projection kernels with an
+    fp32 result, an odd number of columns and K split across workgroups."""
+    shape = WL.LayerShape(H=512, nq=8, nkv=2, d=64, F=688, E=E, k=2)
     wl = WL.Workload("moe", shape, "decode", B=48)
     weights, io, _ = WL.build(wl, seed=2, ctx_lens=[100 + 3 * i for i in range(48)])
     got = run_layer(B, wl, weights, io)
