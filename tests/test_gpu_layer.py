@@ -323,6 +323,90 @@ def test_pipeline_step_micro_batches_of_different_sizes(B):
     assert need >= max(B.ts_layer_workspace_bytes(desc, n, n) for n in (5, 1, 4, 2))
 
 
+@pytest.mark.parametrize("mask", [0xFF, 0b00100100])
+def test_pipeline_step_over_prompts(B, mask):
+    """Prefill through the pipelined step (the paper pipelines whole requests, prompt phase included): micro-batches
+    are packed prompts of different lengths, each with a fresh cache.  Outputs, written caches, shipped boundary
+    bytes and the KV delta (here every prompt token's K and V row) are bit-identical to ts_layer_forward on the
+    micro-batch alone; the shipped bytes match the oracle's boundary tensors within tolerance."""
+    shape = WL.LayerShape(H=512, nq=8, nkv=2, d=64, F=1376)
+    prompts = [[70, 33], [128], [5, 64, 17], [1, 200]]
+    Lcap = 256
+    gen = torch.Generator().manual_seed(21)
+    weights = WL.make_weights(shape, gen)
+    wd = {k: v.to(DEV) for k, v in weights.items()}
+    desc = B.make_desc(shape, Lcap, "prefill")
+    wts = B.make_weights(wd)
+    nb = B.TS_NB_DENSE
+    n_mb = len(prompts)
+    ios, singles, Ts, Bs = [], [], [], []
+    for seqs in prompts:
+        io = WL.make_prefill_io(shape, seqs, gen, Lcap=Lcap)
+        T, nseq = sum(seqs), len(seqs)
+        iod = {k: v.to(DEV) for k, v in io.items()}
+        out = torch.empty(T, shape.H, dtype=torch.bfloat16, device=DEV)
+        ws1 = torch.zeros(B.ts_layer_workspace_bytes(desc, T, nseq), dtype=torch.uint8, device=DEV)
+        iod1 = {k: v.clone() for k, v in iod.items()}
+        B.ts_layer_forward(desc, wts, B.make_io(iod1, out, T, nseq, max(seqs)), ws1)
+        torch.cuda.synchronize()
+        rows = []
+        for j in range(nb):
+            if (mask >> j) & 1:
+                off, nbytes = B.ts_layer_boundary(desc, T, nseq, j)
+                rows.append(out.view(torch.uint8).reshape(-1).clone() if off is None else ws1[off:off + nbytes].clone())
+        singles.append((out.clone(), torch.cat(rows), iod1["kcache"].clone(), iod1["vcache"].clone()))
+        ios.append((io, iod))
+        Ts.append(T)
+        Bs.append(nseq)
+    Tmax, Bmax = max(Ts), max(Bs)
+    stride = B.ts_pipeline_slot_stride(desc, Tmax, Bmax, mask)
+    layouts = [B.ts_pipeline_boundary_layout(desc, Ts[i], Bs[i], mask) for i in range(n_mb)]
+    staging = torch.zeros(stride * n_mb, dtype=torch.uint8, device=DEV)
+    host = torch.zeros(stride * n_mb, dtype=torch.uint8).pin_memory()
+    slot = B.ts_pipeline_workspace_slot_bytes(desc, Ts, Bs)
+    dstride = B.ts_pipeline_kv_delta_stride(desc, Tmax)
+    assert dstride >= Tmax * 2 * shape.nkv * shape.d * 2
+    delta_dev = torch.zeros(dstride * n_mb, dtype=torch.uint8, device=DEV)
+    delta_host = torch.zeros(dstride * n_mb, dtype=torch.uint8).pin_memory()
+    pipe = B.ts_pipeline_create(desc, n_mb)
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    copy, delta_stream = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    try:
+        B.ts_pipeline_set_kv_delta(pipe, delta_stream, delta_dev, delta_host)
+        for rep, (mode, nslot) in enumerate([(B.TS_PIPE_COPY_SIDE_STREAM, 2), (B.TS_PIPE_COPY_COALESCED, 3),
+                                             (B.TS_PIPE_COPY_COALESCED_HALVES, 2), (B.TS_PIPE_COPY_SERIALISED, n_mb)]):
+            ws = torch.zeros(nslot * slot, dtype=torch.uint8, device=DEV)
+            caches = [{k: v.clone() for k, v in ios[i][1].items()} for i in range(n_mb)]
+            outs = [torch.zeros(Ts[i], shape.H, dtype=torch.bfloat16, device=DEV) for i in range(n_mb)]
+            mbs = [B.make_io(caches[i], outs[i], Ts[i], Bs[i], max(prompts[i])) for i in range(n_mb)]
+            host.zero_()
+            delta_host.zero_()
+            torch.cuda.synchronize()
+            B.ts_pipeline_step(pipe, wts, mbs, streams, copy, mask, staging, host, ws, copy_mode=mode)
+            for st in streams + [copy, delta_stream]:
+                st.synchronize()
+            for i in range(n_mb):
+                assert torch.equal(outs[i], singles[i][0]), f"rep {rep} micro-batch {i}: output"
+                assert torch.equal(caches[i]["kcache"], singles[i][2]) and torch.equal(caches[i]["vcache"], singles[i][3])
+                got = host[i * stride:i * stride + layouts[i][-1]]
+                assert torch.equal(got, singles[i][1].cpu()), f"rep {rep} micro-batch {i}: pinned-host boundary bytes"
+                c = caches[i]
+                k_new = c["kcache"][c["seq_id"].long(), :, c["pos"].long(), :].reshape(Ts[i], -1)
+                v_new = c["vcache"][c["seq_id"].long(), :, c["pos"].long(), :].reshape(Ts[i], -1)
+                want = torch.cat([k_new, v_new], dim=1).contiguous().view(torch.uint8).reshape(-1).cpu()
+                assert torch.equal(delta_host[i * dstride:i * dstride + want.numel()], want), f"rep {rep} micro-batch {i}: KV delta"
+    finally:
+        B.ts_pipeline_destroy(pipe)
+    w64 = {k: WL.as_f64(v) for k, v in weights.items()}
+    for i in range(n_mb):
+        r = O.layer_forward(shape, w64, {k: WL.as_f64(v) for k, v in ios[i][0].items()}, "prefill")
+        ref = O.boundary_stream(r, moe=False, mask=mask)
+        got = singles[i][1].view(torch.bfloat16)
+        assert got.numel() == ref.size
+        assert_close(got, ref, f"micro-batch {i} boundary stream")
+
+
 @pytest.mark.parametrize("mask", [0x1FF, 0b010100000, 0])
 def test_pipeline_step_over_a_moe_layer(B, mask):
     """The MoE layer has nine kernel boundaries (the expert outputs before the weighted combine are one of them);
