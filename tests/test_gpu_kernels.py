@@ -236,6 +236,51 @@ def test_attention_decode_seeded_random(B):
         assert_close(out, ref, f"case {case}: nq={nq} nkv={nkv} d={d} lens={lens} Lcap={Lcap}")
 
 
+def test_attention_decode_long_caches_seeded_random(B):
+    """Caches long enough for the balanced split (the keys of all (sequence, kv head) pairs cut into equal
+    ranges, one per workgroup): length mixes with empty sequences, one key, granule boundaries, full caches, one
+    long sequence among short ones, short sequences in a long cache; each case is run twice on the same
+    workspace with the sequences in reverse order the second time (the arrival counters must be back at zero)."""
+    rng = np.random.default_rng(99)
+    for case in range(10):
+        d = int(rng.choice([64, 128]))
+        nkv = int(rng.choice([1, 2, 4]))
+        g_ = int(rng.choice([1, 4, 8, 16]))
+        nq = nkv * g_
+        Bs = int(rng.integers(1, 11))
+        Lcap = int(rng.choice([8200, 12345, 20000]))
+        special = [0, 1, 127, 128, 129, 4096, Lcap - 1, Lcap]
+        kind = case % 4
+        if kind == 0:
+            lens = [int(rng.integers(0, Lcap + 1)) for _ in range(Bs)]
+        elif kind == 1:
+            lens = [int(rng.choice(special)) for _ in range(Bs)]
+        elif kind == 2:
+            lens = [int(rng.integers(0, 200)) for _ in range(Bs)]
+            lens[int(rng.integers(0, Bs))] = Lcap
+        else:
+            lens = [int(rng.integers(1, 600)) for _ in range(Bs)]
+        g = gen(7000 + case)
+        q = WL.randn_bf16(g, Bs, nq, d)
+        kc = WL.randn_bf16(g, Bs, nkv, Lcap, d)
+        vc = WL.randn_bf16(g, Bs, nkv, Lcap, d)
+        ws = ws_bytes(B.ts_attention_decode_workspace_bytes(Bs, nq, nkv, d, Lcap))
+        scale = 1 / math.sqrt(d)
+        qd, kd, vd = dev(q), dev(kc), dev(vc)
+        for rnd in range(2):
+            order = list(range(Bs)) if rnd == 0 else list(range(Bs))[::-1]
+            ls = [lens[i] for i in order]
+            sl = torch.tensor(ls, dtype=torch.int32)
+            out = torch.full((Bs, nq, d), 9.0, dtype=torch.bfloat16, device=DEV)
+            # (the lengths are permuted, the caches are not: sequence b simply attends over another prefix)
+            B.ts_attention_decode(qd, kd, vd, dev(sl), out, Bs, nq, nkv, d, Lcap, scale, ws)
+            ref = O.attention_decode(WL.as_f64(q), WL.as_f32(kc), WL.as_f32(vc), ls, scale)
+            assert_close(out, ref, f"case {case} round {rnd}: nq={nq} nkv={nkv} d={d} lens={ls} Lcap={Lcap}")
+            for b, L in enumerate(ls):
+                if L == 0:
+                    assert torch.all(out[b] == 0), "empty sequence gives a zero row"
+
+
 def test_attention_decode_degenerate(B):
     g = gen(3)
     nq, nkv, d, Lcap = 8, 2, 128, 64
