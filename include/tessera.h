@@ -138,7 +138,11 @@ int ts_rope_table(float* table_host, int table_len, int d, float base);
  * q, out: [B,nq,d]; kcache, vcache: [B,nkv,Lcap,d]; seq_lens: [B] (number of
  * keys attended, the just-appended token included; 0 gives a zero row).
  * Requires d == 64 or d == 128, nq/nkv <= 16, seq_lens[b] <= Lcap.
- * ws: at least ts_attention_decode_workspace_bytes(B,nq,d,Lcap) bytes.
+ * ws: at least ts_attention_decode_workspace_bytes(B,nq,nkv,d,Lcap) bytes (fp32 partial results of
+ * the split over keys and, for long caches, one arrival counter per (sequence, kv head), which
+ * the call clears itself); contents undefined afterwards.  The split is derived on the device from
+ * seq_lens (no host synchronisation); the result does not depend on the order in which workgroups
+ * finish.
  */
 size_t ts_attention_decode_workspace_bytes(int B, int nq, int nkv, int d, int Lcap);
 int ts_attention_decode(const ts_bf16* q, const ts_bf16* kcache, const ts_bf16* vcache,
@@ -148,7 +152,8 @@ int ts_attention_decode(const ts_bf16* q, const ts_bf16* kcache, const ts_bf16* 
 /* The same call for callers that cannot allocate or carry a workspace (code under HIP graph capture, tight
  * serving loops, harnesses that forbid hipMalloc): the split-KV partials live in a device array that is part
  * of the library image, ts_attention_decode_static_limit() bytes (16 MiB) on every GPU the library runs on, held
- * until the process ends.  Same kernels and bit-identical results to ts_attention_decode.  Shapes whose
+ * until the process ends.  Same kernels and bit-identical results to ts_attention_decode (what must start at
+ * zero in the array, the arrival counters, is cleared by a kernel of the call).  Shapes whose
  * partials (ts_attention_decode_workspace_bytes) exceed the limit are rejected with TS_ERR_WORKSPACE before
  * anything is enqueued.  The call allocates and frees nothing.  All calls on one GPU share that GPU's array:
  * calls that may run at the same time on one GPU (different streams) race and must be ordered by the caller. */

@@ -10,8 +10,11 @@
 // output accumulators, so the online-softmax state needs no cross-lane traffic except a
 // 2-step max over the four lane groups.
 //
-// Split-KV: grid (chunk, kv head, sequence); each workgroup reduces its chunk to an
-// un-normalised (m, l, O) triple per head in fp32; a second kernel merges the chunks.
+// Split-KV, two forms.  Short caches: grid (chunk, kv head, sequence), a sequence gets as many equal chunks as
+// its length needs; each workgroup reduces its chunk to an un-normalised (m, l, O) triple per head in fp32
+// and a second kernel merges the chunks (a sequence with one chunk is finished by its workgroup).  Long
+// caches: the balanced form further down, one equal key range per resident workgroup and the merge inside
+// the launch.
 #include <mutex>
 #include "common.hpp"
 
@@ -212,7 +215,6 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(const ts_bf16* _
                                                                 float* __restrict__ part, int q_stride, int nq, int nkv,
                                                                 int Lcap, int NCH, int chunk_target,
                                                                 float c_scale /* scale * log2(e) */,
-                                                                int32_t* __restrict__ counters,
                                                                 ts_bf16* __restrict__ out) {
   constexpr int KSTEPS = D / 32;   // MFMA k-steps for Q.K
   constexpr int DT = D / 16;       // 16-wide output column tiles
@@ -265,38 +267,12 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(const ts_bf16* _
       return;
     }
     float* dst = part + (((size_t)b * nq + (size_t)kvh * g + h) * NCH + ch) * (D + 2);
-    if (counters != nullptr) {   // read by another workgroup of this launch: device-coherent stores
-      st_dev_f32(dst + col, acc);
-      if (col == 0) {
-        st_dev_f32(dst + D, M);
-        st_dev_f32(dst + D + 1, L);
-      }
-    } else {
-      dst[col] = acc;
-      if (col == 0) {
-        dst[D] = M;
-        dst[D + 1] = L;
-      }
+    dst[col] = acc;
+    if (col == 0) {
+      dst[D] = M;
+      dst[D + 1] = L;
     }
   });
-  if (counters == nullptr || nchunk == 1) return;
-
-  // ---- merge fused into this launch: the last chunk of this (sequence, kv head) to arrive
-  // combines all chunks in chunk order (the same arithmetic as attn_decode_merge_kernel) and
-  // re-arms the counter.  Partials travel through device-coherent stores and loads (other chunks
-  // ran on other XCDs); every wave waits for its stores before the arrival is counted.
-  __shared__ int s_last;
-  wait_stores();
-  __syncthreads();
-  if (tid == 0) s_last = (atomicAdd(&counters[b * nkv + kvh], 1) == nchunk - 1);
-  __syncthreads();
-  if (!s_last) return;
-  for (int idx = tid; idx < g * D; idx += 256) {
-    const int h = idx / D, col = idx % D;
-    const float* p = part + ((size_t)b * nq + (size_t)kvh * g + h) * NCH * (D + 2);
-    out[((size_t)b * nq + (size_t)kvh * g + h) * D + col] = f_to_bf(decode_merge_pieces_dev<D>(p, nchunk, col));
-  }
-  if (tid == 0) __hip_atomic_store(&counters[b * nkv + kvh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 // ---------------------------------------------------------------------------------------------------------
@@ -593,19 +569,15 @@ int launch_attention_decode(const ts_bf16* q, int q_stride, const ts_bf16* kc, c
     TS_LAUNCH_CHECK("attn_decode_balanced");
     return TS_OK;
   }
+  // Chunks per sequence: with one chunk the split kernel writes the result itself, else a merge kernel follows.
   dim3 grid((unsigned)NCH * nkv * B);
-  // Merge inside the split kernel (last chunk to arrive) when sequences can have many chunks: the
-  // merge kernel then costs more than the coherent partial traffic (ragged 70B shape: 426 us
-  // against 441 + 18); with one or two chunks the separate kernel is cheaper, with one chunk
-  // there is nothing to merge.
-  if (NCH < 4) counters = nullptr;
-  const bool merge_kernel = counters == nullptr && NCH > 1;
+  const bool merge_kernel = NCH > 1;
   if (d == 128) {
     const size_t stage = (size_t)4 * kBlockKeys * 17 * sizeof(uint4);
     const size_t merge = (size_t)(4 * 16 * 128 + 128) * sizeof(float);
     const size_t smem = stage > merge ? stage : merge;
     TS_LAUNCH_EX(!merge_kernel, "attn_decode_split", attn_decode_split_kernel<128>, grid, dim3(256), smem, s, q, kc, vc, seq_lens, part, q_stride, nq,
-                       nkv, Lcap, NCH, plan.chunk_target, c_scale, counters, out);
+                       nkv, Lcap, NCH, plan.chunk_target, c_scale, out);
     TS_LAUNCH_CHECK("attn_decode_split");
     if (merge_kernel)
       TS_LAUNCH_LAST("attn_decode_merge", attn_decode_merge_kernel<128>, dim3(B * nq), dim3(128), 0, s, part, seq_lens, out, nq, NCH, plan.chunk_target);
@@ -614,7 +586,7 @@ int launch_attention_decode(const ts_bf16* q, int q_stride, const ts_bf16* kc, c
     const size_t merge = (size_t)(4 * 16 * 64 + 128) * sizeof(float);
     const size_t smem = stage > merge ? stage : merge;
     TS_LAUNCH_EX(!merge_kernel, "attn_decode_split", attn_decode_split_kernel<64>, grid, dim3(256), smem, s, q, kc, vc, seq_lens, part, q_stride, nq,
-                       nkv, Lcap, NCH, plan.chunk_target, c_scale, counters, out);
+                       nkv, Lcap, NCH, plan.chunk_target, c_scale, out);
     TS_LAUNCH_CHECK("attn_decode_split");
     if (merge_kernel)
       TS_LAUNCH_LAST("attn_decode_merge", attn_decode_merge_kernel<64>, dim3(B * nq), dim3(64), 0, s, part, seq_lens, out, nq, NCH, plan.chunk_target);
