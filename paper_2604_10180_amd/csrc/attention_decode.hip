@@ -38,9 +38,9 @@ __host__ __device__ __forceinline__ int decode_nchunk(int len, int NCH, int chun
 // o).  vst is the wave's LDS stage.  l_run comes back summed over the four lane groups.
 template <int D>
 __device__ __forceinline__ void decode_wave_range(const U4 (&qf)[D / 32], const ts_bf16* __restrict__ kbase,
-                                                  const ts_bf16* __restrict__ vbase, int start, int end, int wave,
-                                                  int lane, uint4* vst, float c_scale, float& m_run, float& l_run,
-                                                  f32x4 (&o)[D / 16]) {
+                                                  const ts_bf16* __restrict__ vbase, int start, int end, int rot,
+                                                  int wave, int lane, uint4* vst, float c_scale, float& m_run,
+                                                  float& l_run, f32x4 (&o)[D / 16]) {
   constexpr int KSTEPS = D / 32;   // MFMA k-steps for Q.K
   constexpr int DT = D / 16;       // 16-wide output column tiles
   constexpr int CPR = D / 8;       // 16-byte chunks per cache row
@@ -60,8 +60,13 @@ __device__ __forceinline__ void decode_wave_range(const U4 (&qf)[D / 32], const 
   // MFMA operand read straight from global would touch per instruction it is 6.2).  K goes through the wave's
   // LDS stage to reach the operand layout, V follows into the same stage.
   U4 kr[VLOADS], vf[VLOADS];
-  auto load_block = [&](int blk) {
-    const int k0 = start + blk * kBlockKeys;
+  // The blocks are visited from block `rot` on, wrapping around: workgroups that start together would
+  // otherwise sweep their key ranges in step, and with an unlucky distance between the ranges (the cache
+  // capacity sets it) they keep landing on the same memory channels (64 x 2049 keys: 84 us at a capacity of
+  // 2049 or 2176 rows, 97 us at 2064).  The order is a fixed function of the range, so results stay reproducible.
+  auto block_of = [&](int j) { const int t = j + rot; return t >= nblk ? t - nblk : t; };
+  auto load_block = [&](int j) {
+    const int k0 = start + block_of(j) * kBlockKeys;
 #pragma unroll
     for (int i = 0; i < VLOADS; ++i) {
       const int c = lane + 64 * i;
@@ -73,7 +78,7 @@ __device__ __forceinline__ void decode_wave_range(const U4 (&qf)[D / 32], const 
 
   if (wave < nblk) load_block(wave);
   for (int blk = wave; blk < nblk; blk += 4) {
-    const int k0 = start + blk * kBlockKeys;
+    const int k0 = start + block_of(blk) * kBlockKeys;
     // stage K: unpadded rows, 16-byte chunk c of row r at chunk c ^ (r % CPR) (conflict-free row writes and
     // operand reads), read it back as MFMA operands and run the score MFMAs
 #pragma unroll
@@ -258,7 +263,9 @@ __global__ __launch_bounds__(256) void attn_decode_split_kernel(const ts_bf16* _
 
   float m_run, l_run;
   f32x4 o[DT];
-  decode_wave_range<D>(qf, kbase, vbase, start, end, wave, lane, vst, c_scale, m_run, l_run, o);
+  const int nblk_all = (end - start + kBlockKeys - 1) / kBlockKeys;
+  const int rot = nblk_all > 0 ? (int)((blockIdx.x * 2654435761u >> 8) % (unsigned)nblk_all) : 0;
+  decode_wave_range<D>(qf, kbase, vbase, start, end, rot, wave, lane, vst, c_scale, m_run, l_run, o);
 
   // ---- merge the four waves
   decode_combine_waves<D>(smem, tid, g, m_run, l_run, o, [&](int h, int col, float acc, float M, float L) {
@@ -404,7 +411,8 @@ __global__ __launch_bounds__(256) void attn_decode_balanced_kernel(const ts_bf16
     const ts_bf16* vbase = vc + ((size_t)b * nkv + kvh) * (size_t)Lcap * D;
     float m_run, l_run;
     f32x4 o[DT];
-    decode_wave_range<D>(qf, kbase, vbase, start, end, wave, lane, vst, c_scale, m_run, l_run, o);
+    // (no rotated block order here: the ranges start at unrelated places of unrelated pairs already)
+    decode_wave_range<D>(qf, kbase, vbase, start, end, 0, wave, lane, vst, c_scale, m_run, l_run, o);
 
     const size_t row0 = (size_t)b * nq + (size_t)kvh * g;
     const bool slot_ok = piece >= 0 && piece < NCH;   // holds by the choice of `workers`; never write outside the buffer
