@@ -145,8 +145,8 @@ LayerPlan plan_layer(const ts_layer_desc& d, int T, int B) {
   if (d.mode == TS_MODE_DECODE) mx(attention_decode_workspace_bytes(B, d.nq, d.nkv, d.d, d.Lcap));
   p.scratch_bytes = sc;
   p.scratch = take(sc);
-  // arrival counters of the in-kernel chunk merge of decode attention (one per sequence and kv
-  // head); the kernel leaves its words zeroed
+  // arrival counters of the merge inside the balanced form of decode attention (one per sequence and kv
+  // head): cleared by the layer's first kernel, re-armed by the workgroup that merges
   int cw = 0;
   if (d.mode == TS_MODE_DECODE) cw = B * d.nkv;
   p.counter_words = cw;
